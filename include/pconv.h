@@ -1,0 +1,155 @@
+/*
+ * pconv.h - C ABI of the MI355X (gfx950) PCONV sparse 3x3 convolution library.
+ *
+ * PCONV weights carry two kinds of sparsity (paper, "Theory of Sparse Convolution
+ * Patterns"): every surviving 3x3 kernel keeps only the taps of one binary mask, its
+ * Sparse Convolution Pattern, drawn from a small per-layer pattern table; and whole
+ * kernels, i.e. (output filter f, input channel c) connections, are removed
+ * (connectivity pruning).  The layer computes the ordinary un-flipped DNN convolution,
+ * Eq. (1) of "The Convolution Operator", over those masked weights:
+ *
+ *   Y[n,f,y,x] = act( b[f] + sum_c sum_r sum_s  W[f,c,r,s] * P_{pid[f,c]}[r,s] * conn[f,c]
+ *                                                * Xpad[n, c, y*stride + r - pad, x*stride + s - pad] )
+ *
+ * Xpad is X inside the image and 0 outside; act is ReLU or identity.
+ *
+ * All functions return PCONV_OK (0) or a negative pconv_status; no C++ exception crosses
+ * this boundary.  A human-readable message for the last failing call of the calling thread
+ * is available from pconv_last_error().  "host" / "device" below says where a pointer must
+ * live; device pointers must belong to the HIP device that is current at the call.
+ */
+#ifndef PCONV_H
+#define PCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pconv_handle pconv_handle;   /* opaque; owns its host and device buffers */
+
+typedef enum { PCONV_F32 = 0, PCONV_BF16 = 1 } pconv_dtype;
+typedef enum { PCONV_NCHW = 0, PCONV_NHWC = 1 } pconv_layout;
+
+typedef enum {
+    PCONV_OK = 0,
+    PCONV_INVALID_ARG = -1,   /* null pointer, bad dimension, bad mask, bad pattern id, ... */
+    PCONV_OOM = -2,           /* host or device allocation failed                            */
+    PCONV_HIP_ERROR = -3,     /* a HIP runtime call failed (message has the HIP error name)  */
+    PCONV_UNSUPPORTED = -4    /* valid request this build has no kernel for                  */
+} pconv_status;
+
+enum { PCONV_MAX_PATTERNS = 16 };
+
+/*
+ * pconv_pack - the offline compiler stage of the paper ("Compiler-assisted DNN Inference
+ * Framework": layer-wise information extraction, filter kernel reorder, compact storage),
+ * run on the host.  Synchronous.
+ *
+ *   w_dense      host, [c_out][c_in][3][3] fp32 (OIHW).  Values under a cleared mask bit or
+ *                on a removed kernel are ignored; kept values are copied bit for bit
+ *                (fp32) or rounded to nearest-even bf16 (weight_dtype == PCONV_BF16).
+ *   pattern_id   host, [c_out][c_in]; index into table; ignored where conn == 0.
+ *   conn         host, [c_out][c_in]; 0 = kernel removed, non-zero = kept.
+ *   table        host, [num_patterns]; 9-bit masks, bit (3*r + s) keeps tap (r, s).
+ *                Any non-zero mask <= 0x1FF is legal (0x1FF = dense kernel).
+ *   num_patterns 1 .. PCONV_MAX_PATTERNS;  c_out, c_in in 1 .. 65535.
+ *   out          receives a new handle (valid only when PCONV_OK is returned).
+ *
+ * The caller keeps ownership of every input; everything needed is copied.  The packed
+ * weights are uploaded to the current HIP device.  Filters with no kept kernel are legal.
+ * Errors: PCONV_INVALID_ARG (null pointers, sizes out of range, mask == 0 or > 0x1FF,
+ * pattern_id >= num_patterns on a kept kernel), PCONV_OOM, PCONV_HIP_ERROR.
+ */
+int pconv_pack(const float *w_dense, const uint8_t *pattern_id, const uint8_t *conn,
+               const uint16_t *table, int num_patterns, int c_out, int c_in,
+               pconv_dtype weight_dtype, pconv_handle **out);
+
+/*
+ * pconv_conv2d - the sparse convolution itself (Eq. (1) over the packed weights; the
+ * "load redundancy elimination" stage of the paper: only inputs under kept taps of kept
+ * kernels are touched).  Asynchronous on hip_stream; allocates nothing; the handle is
+ * read-only, so concurrent calls on one handle are safe.
+ *
+ *   x_dev     device, activations [n][c_in][h_in][w_in] (NCHW) or [n][h_in][w_in][c_in]
+ *             (NHWC), fp32 or bf16 as act_dtype says.
+ *   y_dev     device, output in the same layout and dtype with c_out channels and
+ *             h_out = (h_in + 2*pad - 3)/stride + 1 (same for w).  Must not alias x_dev.
+ *   bias_dev  device, [c_out] fp32, or NULL for no bias.
+ *   stride    1 or 2;  pad must be 1;  fuse_relu != 0 applies max(., 0) after the bias.
+ *   act_dtype must equal the handle's weight dtype.  Products are accumulated in fp32;
+ *             bf16 outputs are rounded to nearest even.
+ *   hip_stream  a hipStream_t, or NULL for the default stream.
+ *
+ * Errors: PCONV_INVALID_ARG (null pointers, n/h/w <= 0, stride not in {1,2}, pad != 1,
+ * dtype mismatch, tensors of 2^31 elements or more), PCONV_HIP_ERROR (launch failed).
+ */
+int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
+                 int n, int h_in, int w_in, int stride, int pad,
+                 pconv_layout layout, pconv_dtype act_dtype, int fuse_relu, void *hip_stream);
+
+/* pconv_free - releases the handle's host and device memory.  NULL is allowed. */
+void pconv_free(pconv_handle *h);
+
+/*
+ * pconv_maxpool2x2 - plain 2x2 / stride-2 max-pool used between VGG-16 blocks (not part of
+ * the paper's method; a helper so a whole 3x3 stack can be chained on the device).
+ *   x_dev [n][c][h][w] or [n][h][w][c] -> y_dev with h/2, w/2 (floor).  Asynchronous.
+ */
+int pconv_maxpool2x2(const void *x_dev, void *y_dev, int n, int c, int h, int w,
+                     pconv_layout layout, pconv_dtype dtype, void *hip_stream);
+
+/* ---- inspection of a handle (tests, benchmarks) --------------------------------------- */
+
+typedef struct {
+    int32_t c_out, c_in, num_patterns, weight_dtype;
+    int64_t kept_kernels;      /* K   = number of kept (f, c) pairs                        */
+    int64_t nnz;               /* sum over kept kernels of popcount(mask)                  */
+    int64_t device_bytes;      /* device memory held by the handle                         */
+    int32_t fast_path;         /* 1 if the register-tiled kernel can serve this handle     */
+    int32_t reserved;
+} pconv_info;
+
+int pconv_get_info(const pconv_handle *h, pconv_info *info);
+
+/*
+ * pconv_debug_export - copies out the canonical logical layout produced by the filter
+ * kernel reorder, for bit-exact comparison.  All outputs are caller-allocated host arrays:
+ *   perm[c_out]            filter at each position; filters sorted by (kept-kernel count
+ *                          descending, per-pattern counts descending in pattern order,
+ *                          filter index ascending)
+ *   row_ptr[c_out + 1]     first kernel of each position; row_ptr[c_out] = K
+ *   pat_cnt[c_out][P]      kernels per pattern at each position
+ *   cin[K]                 input channel of each kernel; inside a filter kernels are ordered
+ *                          by (pattern id, input channel)
+ *   vals[nnz]              kept weights of each kernel in ascending tap order; fp32 bit
+ *                          copies, or uint16 bf16 bit patterns for a bf16 handle
+ */
+int pconv_debug_export(const pconv_handle *h, uint16_t *perm, uint32_t *row_ptr,
+                       uint16_t *pat_cnt, uint16_t *cin, void *vals);
+
+/* pconv_debug_pack_host - the host stages of pconv_pack only (analysis, reorder, compact
+ * storage) with no upload, so the packing logic can be checked on a machine without a GPU.
+ * The handle works with pconv_get_info, pconv_debug_export and pconv_free; pconv_conv2d and
+ * pconv_debug_unpack reject it with PCONV_INVALID_ARG.  Arguments as for pconv_pack. */
+int pconv_debug_pack_host(const float *w_dense, const uint8_t *pattern_id, const uint8_t *conn,
+                          const uint16_t *table, int num_patterns, int c_out, int c_in,
+                          pconv_dtype weight_dtype, pconv_handle **out);
+
+/* pconv_debug_unpack - rebuilds dense masked weights [c_out][c_in][3][3] fp32 on the host
+ * from the DEVICE copy of the packed data (zeros where nothing is stored). */
+int pconv_debug_unpack(const pconv_handle *h, float *w_dense_out);
+
+/* Kernel selection, for tests and benchmarks: 0 = automatic (default), 1 = always the
+ * generic gather kernel, 2 = require the register-tiled kernel (PCONV_UNSUPPORTED if the
+ * handle or the call cannot use it).  Process-wide. */
+int pconv_set_kernel_policy(int policy);
+
+const char *pconv_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PCONV_H */

@@ -1,0 +1,80 @@
+// Internal declarations shared by the host packer, the kernels' launchers and the C ABI.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "pconv.h"
+
+namespace pconv {
+
+// Thread-local message for pconv_last_error().
+void set_error(const std::string &msg);
+const char *get_error();
+
+// Result of the host-side analysis + reorder (paper: layer-wise information extraction and
+// filter kernel reorder).  "Position" i means the i-th filter in the sorted order.
+struct Canonical {
+    std::vector<uint16_t> perm;      // [F]     filter at position i
+    std::vector<uint32_t> row_ptr;   // [F+1]   first kernel of position i
+    std::vector<uint16_t> pat_cnt;   // [F][P]  kernels per pattern at position i
+    std::vector<uint16_t> cin;       // [K]     input channel of kernel k
+    std::vector<uint8_t>  pat;       // [K]     pattern id of kernel k (derivable from pat_cnt)
+    std::vector<uint32_t> val_ptr;   // [K+1]   first stored weight of kernel k
+    std::vector<uint32_t> vals_bits; // [nnz]   fp32 bit patterns (bf16 handles: value << 16)
+};
+
+// Device-side stream of the register-tiled kernel.  Filters are dealt into blocks of kTileFB
+// filters ("slots"); for every (block, input channel) the records of that channel are stored
+// contiguously, ordered by slot.  A record is one code (sub-mask with a specialised inner
+// loop) of one kernel, with up to four weights in ascending tap order.
+struct TiledStream {
+    int num_blocks = 0;                 // ceil(F / kTileFB)
+    int row_len = 0;                    // entries per chan_ptr row: round_up(C, kTileCH) + 1
+    std::vector<int32_t>  slot_filter;  // [num_blocks * kTileFB] original filter index or -1
+    std::vector<uint32_t> chan_ptr;     // [num_blocks][row_len]
+    std::vector<uint32_t> meta;         // [R] slot * kNumCodes + code
+    std::vector<float>    w4;           // [R][4]
+};
+
+}  // namespace pconv
+
+struct pconv_handle {
+    int c_out = 0, c_in = 0, np = 0, wdtype = 0, device = -1;
+    uint16_t table[PCONV_MAX_PATTERNS] = {0};
+    int64_t K = 0, nnz = 0, device_bytes = 0;
+    pconv::Canonical canon;
+    pconv::TiledStream tiled;
+    // device copies (generic gather kernel)
+    int32_t  *d_perm = nullptr;
+    uint32_t *d_row_ptr = nullptr;
+    uint32_t *d_kern = nullptr;      // [K] cin | mask << 16
+    uint32_t *d_val_ptr = nullptr;   // [K]
+    float    *d_vals = nullptr;      // [nnz] fp32 (bf16 weights widened exactly)
+    // device copies (register-tiled kernel)
+    int32_t  *d_slot_filter = nullptr;
+    uint32_t *d_chan_ptr = nullptr;
+    uint32_t *d_meta = nullptr;
+    float    *d_w4 = nullptr;
+};
+
+namespace pconv {
+
+// Host analysis + reorder.  Returns PCONV_OK or an error status (message set).
+int build_canonical(const float *w, const uint8_t *pid, const uint8_t *conn, const uint16_t *table,
+                    int np, int c_out, int c_in, int wdtype, Canonical &out);
+
+void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int c_out, int c_in,
+                        TiledStream &out);
+
+// Kernel launchers (pconv_kernels.hip, pconv_tiled.hip).  All return a pconv_status.
+int launch_conv_generic(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
+                        int hin, int win, int stride, int layout, int dtype, int relu, void *stream);
+int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
+                      int hin, int win, int stride, int layout, int dtype, int relu, void *stream);
+bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype);
+int launch_maxpool2x2(const void *x, void *y, int n, int c, int h, int w, int layout, int dtype,
+                      void *stream);
+
+}  // namespace pconv

@@ -1,0 +1,244 @@
+"""GPU parity: pconv_conv2d (through the C ABI) against the CPU oracle, element by element.
+
+Bar: packing and indices bit exact; fp32 outputs within 1e-4 * S, bf16 within 2e-2 * S, where
+S = |bias| + sum |w||x| of that output.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_1909_05073_amd as P
+from pconv_inputs import LayerSpec, base_seed, config_layers, make_input, make_layer
+
+from gpu_util import (assert_close, gather_points, gpu_conv, oracle_full, sample_points, say,
+                      to_device)
+
+pytestmark = pytest.mark.gpu
+
+POLICIES = [1, 0]          # 1 = generic gather kernel, 0 = automatic (register-tiled where possible)
+
+
+@pytest.fixture(autouse=True)
+def _reset_policy():
+    yield
+    P.pconv_set_kernel_policy(0)
+
+
+def check_full(spec, L, x, dtype, layout="nchw", stride=1, relu=False, use_bias=True, policy=0, what=""):
+    say(f"[case] {what or spec.name} dtype={dtype} layout={layout} stride={stride} relu={relu} "
+        f"policy={policy} x={x.shape}")
+    P.pconv_set_kernel_policy(policy)
+    y, h = gpu_conv(L, x, dtype, layout, stride, relu, use_bias)
+    yr, sr = oracle_full(L, x, dtype, layout, stride, relu, use_bias)
+    assert y.shape == yr.shape
+    r = assert_close(y, yr, sr, dtype, what or spec.name)
+    h.free()
+    return r
+
+
+@pytest.mark.parametrize("policy", POLICIES)
+def test_config1_small_layer(policy):
+    spec = config_layers(1)[0]
+    L = make_layer(spec, base_seed(1)); x = make_input(spec, base_seed(1))
+    check_full(spec, L, x, "f32", relu=False, policy=policy)
+    check_full(spec, L, x, "f32", relu=True, use_bias=False, policy=policy)
+
+
+@pytest.mark.parametrize("policy", POLICIES)
+def test_config2_vgg_layer(policy):
+    spec = config_layers(2)[0]
+    L = make_layer(spec, base_seed(2)); x = make_input(spec, base_seed(2))
+    check_full(spec, L, x, "f32", policy=policy)
+
+
+def test_config3_vgg_stack_batch1_layerwise():
+    """Every VGG-16 conv shape at batch 1 with fresh inputs, full output, ReLU fused."""
+    for i, spec in enumerate(config_layers(3, batch=1)):
+        L = make_layer(spec, base_seed(3) + 100 * i); x = make_input(spec, base_seed(3) + 100 * i)
+        check_full(spec, L, x, "f32", relu=True)
+
+
+def test_config3_vgg_chained_with_maxpool_batch2():
+    """conv -> ReLU -> ... -> 2x2 max-pool chained on the device; each layer is checked against
+    the oracle fed with the GPU's own previous activation, so tolerances do not compound."""
+    import torch
+    specs = config_layers(3, batch=2)
+    x = make_input(specs[0], base_seed(3))
+    cur = torch.from_numpy(x).cuda()
+    for i, spec in enumerate(specs):
+        L = make_layer(spec, base_seed(3) + 100 * i)
+        say(f"[case] chained {spec.name} in={tuple(cur.shape)}")
+        h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
+        b = torch.from_numpy(L["bias"]).cuda()
+        y = P.conv2d(h, cur, b, relu=True)
+        torch.cuda.synchronize()
+        xin = cur.cpu().numpy()
+        wt = oracle.masked_weights(L["w"], L["pattern_id"], L["conn"], L["table"])
+        rng = np.random.default_rng(i)
+        pts = sample_points(rng, 2, spec.c_out, spec.h, spec.w, 3000)
+        yr, sr = oracle.conv2d_points(xin, wt, pts, L["bias"], relu=True)
+        assert_close(gather_points(y.cpu().numpy().astype(np.float64), pts, "nchw"), yr, sr, "f32", spec.name)
+        h.free()
+        if spec.pool_after:
+            p = P.maxpool2x2(y)
+            torch.cuda.synchronize()
+            assert np.array_equal(p.cpu().numpy(), oracle.maxpool2x2(y.cpu().numpy()))
+            cur = p
+        else:
+            cur = y
+    assert tuple(cur.shape) == (2, 512, 7, 7)
+
+
+@pytest.mark.parametrize("idx", [1, 5, 9, 12])
+def test_config3_vgg_batch32_sampled(idx):
+    """Bench launch configuration (batch 32) on sampled outputs the oracle computes one by one."""
+    spec = config_layers(3, batch=32)[idx]
+    L = make_layer(spec, base_seed(3) + 100 * idx); x = make_input(spec, base_seed(3) + 100 * idx)
+    say(f"[case] {spec.name} N=32 sampled")
+    y, h = gpu_conv(L, x, "f32", relu=True)
+    wt = oracle.masked_weights(L["w"], L["pattern_id"], L["conn"], L["table"])
+    pts = sample_points(np.random.default_rng(idx), 32, spec.c_out, spec.h, spec.w, 20000)
+    yr, sr = oracle.conv2d_points(x, wt, pts, L["bias"], relu=True)
+    assert_close(gather_points(y, pts, "nchw"), yr, sr, "f32", spec.name)
+    h.free()
+
+
+def test_config4_resnet_bf16():
+    """All sixteen ResNet-50 3x3 layers (stride 2 included), bf16 in/out, fp32 accumulate."""
+    seen = set()
+    for i, spec in enumerate(config_layers(4, batch=32)):
+        key = (spec.c_in, spec.h, spec.stride)
+        L = make_layer(spec, base_seed(4) + i); x = make_input(spec, base_seed(4) + i)
+        say(f"[case] {spec.name} N=32 bf16 sampled")
+        y, h = gpu_conv(L, x, "bf16", stride=spec.stride, relu=True)
+        wt = oracle.masked_weights(L["w"], L["pattern_id"], L["conn"], L["table"], "bf16")
+        pts = sample_points(np.random.default_rng(i), 32, spec.c_out, spec.h_out, spec.w_out, 8000)
+        yr, sr = oracle.conv2d_points(x, wt, pts, L["bias"], stride=spec.stride, relu=True)
+        assert_close(gather_points(y, pts, "nchw"), yr, sr, "bf16", spec.name)
+        if key not in seen:                      # full-output check at batch 2 once per shape
+            seen.add(key)
+            check_full(spec, L, x[:2], "bf16", stride=spec.stride, relu=True, what=spec.name + "_n2")
+        h.free()
+
+
+def test_config5_stress_imbalanced():
+    spec = config_layers(5)[0]
+    L = make_layer(spec, base_seed(5)); x = make_input(spec, base_seed(5))
+    say("[case] config5 N=64 sampled")
+    y, h = gpu_conv(L, x, "f32")
+    wt = oracle.masked_weights(L["w"], L["pattern_id"], L["conn"], L["table"])
+    pts = sample_points(np.random.default_rng(5), 64, 512, 28, 28, 30000)
+    # every filter's first pixel too: heavy and near-empty filters alike
+    allf = np.array([(63, f, 27, 27) for f in range(512)], np.int32)
+    pts = np.concatenate([pts, allf])
+    yr, sr = oracle.conv2d_points(x, wt, pts, L["bias"])
+    assert_close(gather_points(y, pts, "nchw"), yr, sr, "f32", spec.name)
+    check_full(spec, L, x[:2], "f32", what="config5_n2")
+    check_full(spec, L, x[:1], "f32", policy=1, what="config5_n1_generic")
+    h.free()
+
+
+EDGE_SHAPES = [  # (n, c_in, c_out, h, w)
+    (1, 1, 1, 1, 1), (2, 3, 5, 5, 3), (1, 8, 8, 13, 13), (3, 5, 17, 7, 9), (1, 16, 9, 4, 33),
+    (2, 7, 64, 14, 14), (1, 9, 70, 30, 18), (1, 4, 8, 3, 70),
+]
+
+
+@pytest.mark.parametrize("policy", POLICIES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", ["nchw", "nhwc"])
+@pytest.mark.parametrize("stride", [1, 2])
+def test_ragged_shapes_layouts_strides(policy, dtype, layout, stride):
+    for j, (n, ci, co, h, w) in enumerate(EDGE_SHAPES):
+        spec = LayerSpec(f"edge{j}", n, ci, co, h, w, stride=stride, dtype=dtype, num_patterns=12,
+                         pattern_dist="uniform", keep_div=2.0, count_dist="bernoulli")
+        L = make_layer(spec, 1000 + j); x = make_input(spec, 1000 + j, layout)
+        check_full(spec, L, x, dtype, layout, stride, relu=bool(j & 1), use_bias=bool(j & 2), policy=policy)
+
+
+@pytest.mark.parametrize("policy", POLICIES)
+def test_degenerate_filters_and_mixed_masks(policy):
+    rng = np.random.default_rng(7)
+    f, c = 20, 12
+    table = np.array([0x1FF, 0x010, 0x03A, 0x145, 0x0B2, 0x001, 0x100], np.uint16)
+    L = dict(w=rng.standard_normal((f, c, 3, 3)).astype(np.float32),
+             bias=rng.standard_normal(f).astype(np.float32),
+             pattern_id=rng.integers(0, len(table), (f, c)).astype(np.uint8),
+             conn=rng.integers(0, 2, (f, c)).astype(np.uint8), table=table)
+    L["conn"][3] = 0; L["conn"][11] = 0      # filters with no kernel: output = act(bias)
+    L["conn"][5] = 1                          # filter with every kernel
+    spec = LayerSpec("mixed", 2, c, f, 9, 10)
+    x = make_input(spec, 5) - 0.4
+    check_full(spec, L, x, "f32", relu=False, policy=policy, what="mixed masks")
+    check_full(spec, L, x, "f32", relu=True, stride=2, policy=policy, what="mixed masks s2")
+    L["conn"][:] = 0                          # nothing kept at all
+    check_full(spec, L, x, "f32", relu=False, policy=policy, what="empty layer")
+
+
+def test_dense_mask_equals_library_conv():
+    """All-ones mask + full connectivity on the GPU against a library dense convolution."""
+    import torch
+    rng = np.random.default_rng(2)
+    w = rng.standard_normal((16, 6, 3, 3)).astype(np.float32)
+    x = rng.standard_normal((2, 6, 12, 20)).astype(np.float32)
+    L = dict(w=w, bias=np.zeros(16, np.float32), pattern_id=np.zeros((16, 6), np.uint8),
+             conn=np.ones((16, 6), np.uint8), table=np.array([0x1FF], np.uint16))
+    y, h = gpu_conv(L, x, "f32", use_bias=False)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), padding=1)
+    s = torch.nn.functional.conv2d(torch.from_numpy(x).double().abs(), torch.from_numpy(w).double().abs(),
+                                   padding=1)
+    assert_close(y, ref.numpy(), s.numpy(), "f32", "dense")
+    h.free()
+
+
+def test_device_pack_bit_exact_and_unpack_roundtrip():
+    for cfg, dtype in [(2, "f32"), (5, "f32"), (4, "bf16")]:
+        spec = config_layers(cfg)[0]
+        L = make_layer(spec, base_seed(cfg))
+        say(f"[case] pack cfg{cfg} {dtype}")
+        h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], dtype)
+        got = P.pconv_debug_export(h)
+        ref = oracle.pack(L["w"], L["pattern_id"], L["conn"], L["table"], dtype)
+        for k in ("perm", "row_ptr", "pat_cnt", "cin", "vals"):
+            assert got[k].tobytes() == ref[k].tobytes(), k
+        wt = oracle.masked_weights(L["w"], L["pattern_id"], L["conn"], L["table"], dtype).astype(np.float32)
+        assert np.array_equal(P.pconv_debug_unpack(h).view(np.uint32), wt.view(np.uint32))
+        info = h.info()
+        assert info.device_bytes > 0 and info.nnz == len(ref["vals"])
+        h.free()
+
+
+def test_run_to_run_bit_identical_and_stream():
+    import torch
+    spec = config_layers(2)[0]
+    L = make_layer(spec, base_seed(2)); x = make_input(spec, base_seed(2))
+    h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
+    xd = to_device(x, "f32"); b = torch.from_numpy(L["bias"]).cuda()
+    y0 = P.conv2d(h, xd, b).clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        y1 = P.conv2d(h, xd, b)
+    side.synchronize()
+    y2 = P.conv2d(h, xd, b)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1) and torch.equal(y0, y2)
+    h.free()
+
+
+def test_gpu_argument_errors():
+    import torch
+    spec = config_layers(1)[0]
+    L = make_layer(spec, base_seed(1))
+    h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
+    x = torch.zeros(1, 16, 16, 16, device="cuda"); y = torch.zeros_like(x)
+    with pytest.raises(P.PconvError) as e:
+        P.pconv_conv2d(h, x.data_ptr(), y.data_ptr(), 0, 1, 16, 16, act_dtype=P.BF16)
+    assert e.value.status == P.INVALID_ARG
+    with pytest.raises(P.PconvError):
+        P.pconv_conv2d(h, x.data_ptr(), y.data_ptr(), 0, 1, 16, 16, stride=4)
+    with pytest.raises(P.PconvError):
+        P.pconv_conv2d(h, x.data_ptr(), y.data_ptr(), 0, 1 << 20, 1 << 10, 1 << 10)
+    P.pconv_conv2d(h, x.data_ptr(), y.data_ptr(), 0, 1, 16, 16)     # still usable afterwards
+    torch.cuda.synchronize()
+    h.free()
