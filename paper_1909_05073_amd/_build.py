@@ -1,6 +1,7 @@
 """Build the HIP library in-tree: paper_1909_05073_amd/libpconv.so (gfx950 only)."""
 import os
 import subprocess
+import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -38,11 +39,16 @@ def _run(cmd):
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
+    gen_dir = os.path.join(HERE, "_build", "gen")
+    os.makedirs(gen_dir, exist_ok=True)
+    # the record loop of the tiled kernel is generated assembly text
+    subprocess.run([sys.executable, os.path.join(CSRC, "gen_tiled_compute.py"),
+                    os.path.join(gen_dir, "pconv_tiled_compute.inc")], check=True)
     for src in sources():
         obj = os.path.join(HERE, "_build", os.path.basename(src) + ".o")
         os.makedirs(os.path.dirname(obj), exist_ok=True)
         cmd = [hipcc, *HIP_FLAGS, *EXTRA_FLAGS.get(os.path.basename(src), []),
-               "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c"]
+               "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-I", gen_dir, "-c"]
         if src.endswith(".cpp"):
             cmd += ["-x", "hip"]
         cmd += [src, "-o", obj]

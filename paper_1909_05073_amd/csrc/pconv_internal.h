@@ -34,8 +34,8 @@ struct TiledStream {
     int row_len = 0;                    // entries per chan_ptr row: round_up(C, kTileCH) + 1
     std::vector<int32_t>  slot_filter;  // [num_blocks * kTileFB] original filter index or -1
     std::vector<uint32_t> chan_ptr;     // [num_blocks][row_len]
-    std::vector<uint32_t> meta;         // [R] slot * kNumCodes + code
-    std::vector<float>    w4;           // [R][4]
+    std::vector<uint32_t> meta;         // [R+1] record words (see pconv_tiled_codes.h), one pad
+    std::vector<float>    w4;           // [R+1][4]
 };
 
 }  // namespace pconv

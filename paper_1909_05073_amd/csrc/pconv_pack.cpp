@@ -174,11 +174,14 @@ void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int 
         uint32_t *row = &out.chan_ptr[size_t(b) * out.row_len];
         for (int c = 0; c < c_in; ++c) {
             row[c] = uint32_t(out.meta.size());
+            bool first = true;
             for (int s = 0; s < FB; ++s) {
                 const int32_t k = by_slot[s][c];
                 if (k < 0) continue;
                 for (const Piece &pc : pieces[cn.pat[k]]) {
-                    out.meta.push_back(uint32_t(s * kNumCodes + pc.code));
+                    out.meta.push_back(uint32_t(s * kNumCodes + pc.code) | uint32_t(c % kTileCH) << 8 |
+                                       (first ? kMetaFirstOfChannel : 0u));
+                    first = false;
                     for (int j = 0; j < 4; ++j) {
                         float v = 0.0f;
                         if (j < pc.ntaps) std::memcpy(&v, &cn.vals_bits[cn.val_ptr[k] + pc.tap_rank[j]], 4);
@@ -189,6 +192,9 @@ void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int 
         }
         for (int c = c_in; c <= cpad; ++c) row[c] = uint32_t(out.meta.size());
     }
+    // one padding record: the kernel reads record k+1 while it executes record k
+    out.meta.push_back(0u);
+    for (int j = 0; j < 4; ++j) out.w4.push_back(0.0f);
 }
 
 }  // namespace pconv

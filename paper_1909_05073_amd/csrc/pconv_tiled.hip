@@ -13,6 +13,7 @@
 // (slot, code), all register indices are compile-time constants (paper: per-pattern generated
 // code, branch per kernel instead of per weight; here by template instantiation).
 #include <hip/hip_runtime.h>
+#include <cstdlib>
 
 #include "pconv_internal.h"
 #include "pconv_tiled_codes.h"
@@ -38,38 +39,9 @@ __device__ __forceinline__ void st_act(bf16_t *p, size_t i, float v)
     p[i].bits = uint16_t(r);
 }
 
-// 16 FMAs per kept tap of MASK on the 4x4 outputs of one slot.  in[] is the 6x6 neighbourhood
-// (row-major, in[(i+r)*6 + (k+s)] is the input under tap (r,s) of output (i,k)).
-template <unsigned MASK>
-__device__ __forceinline__ void mac_code(float (&acc)[16], const float (&in)[36], const float4 &wv)
-{
-    const float w[4] = {wv.x, wv.y, wv.z, wv.w};
-    int j = 0;
-#pragma unroll
-    for (int t = 0; t < 9; ++t) {
-        if (MASK & (1u << t)) {
-            const int r = t / 3, s = t % 3;
-            const float wt = w[j];
-            ++j;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    acc[i * 4 + k] = fmaf(wt, in[(i + r) * 6 + (k + s)], acc[i * 4 + k]);
-        }
-    }
-}
+typedef float v16f __attribute__((ext_vector_type(16)));
 
-#define PCONV_CODE_CASE(S, C) \
-    case (S) * kNumCodes + (C): mac_code<kCodeMask[C]>(acc[S], in, wv); break;
-#define PCONV_SLOT_CASES(S)                                                                        \
-    PCONV_CODE_CASE(S, 0) PCONV_CODE_CASE(S, 1) PCONV_CODE_CASE(S, 2) PCONV_CODE_CASE(S, 3)        \
-    PCONV_CODE_CASE(S, 4) PCONV_CODE_CASE(S, 5) PCONV_CODE_CASE(S, 6) PCONV_CODE_CASE(S, 7)        \
-    PCONV_CODE_CASE(S, 8) PCONV_CODE_CASE(S, 9) PCONV_CODE_CASE(S, 10) PCONV_CODE_CASE(S, 11)      \
-    PCONV_CODE_CASE(S, 12) PCONV_CODE_CASE(S, 13) PCONV_CODE_CASE(S, 14) PCONV_CODE_CASE(S, 15)    \
-    PCONV_CODE_CASE(S, 16) PCONV_CODE_CASE(S, 17) PCONV_CODE_CASE(S, 18) PCONV_CODE_CASE(S, 19)    \
-    PCONV_CODE_CASE(S, 20) PCONV_CODE_CASE(S, 21) PCONV_CODE_CASE(S, 22) PCONV_CODE_CASE(S, 23)
-static_assert(kNumCodes == 24 && FB == 8, "the case list below is written for 24 codes x 8 slots");
+static_assert(kNumCodes == 24 && FB == 8 && CH == 8, "gen_tiled_compute.py is written for 24 codes, 8 slots, 8-channel chunks");
 
 struct TiledArgs {
     const void *x; void *y; const float *bias;
@@ -77,7 +49,7 @@ struct TiledArgs {
     int n_img, c_in, row_len, h, w, c_out;
     int py, px;                 // patches per image column / row
     int n_patches, n_tiles, n_groups, n_blocks;
-    int relu;
+    int relu, dbg;
 };
 
 template <typename T, int LAYOUT>
@@ -117,87 +89,145 @@ conv_tiled_kernel(const TiledArgs a)
     const int prem = pvalid ? pidx - n * per_img : 0;
     const int y0 = (prem / a.px) * 4, x0 = (prem % a.px) * 4;
 
-    float acc[FB][16];
+    // accumulators: slot s, output (row i, column k) of the patch = acc[s][4 * i + k].  The record
+    // loop below is assembly with a fixed register map, so each vector is pinned to its registers.
+    v16f acc[FB];
 #pragma unroll
-    for (int s = 0; s < FB; ++s)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[s][i] = 0.0f;
+    for (int s = 0; s < FB; ++s) acc[s] = 0.0f;
+    // per-lane LDS byte addresses of this lane's patch inside a staged buffer (128-bit / 64-bit part)
+    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
+    const uint32_t lane_a = lds_base + uint32_t(lane) * 16u;
+    const uint32_t lane_b = lds_base + 1024u + uint32_t(lane) * 8u;
 
-    const int n_chunks = (a.c_in + CH - 1) / CH;
-    for (int chunk = 0; chunk < n_chunks; ++chunk) {
-        const int c0 = chunk * CH;
-        float *buf = lds + (chunk & 1) * BUF_FLOATS;
-
-        // ---- stage: every thread fills 6 (channel, row) segments of its lane's patch ----
-        // Branch-free: out-of-image reads are redirected to element 0 of the tensor and the value
-        // is replaced by zero afterwards, so that all loads of a thread are in flight together.
-        float v[6][6];
+    // ---- staging helpers: every thread owns 6 (channel, row) segments of its lane's patch ----
+    // Loads are branch-free: an out-of-image element reads element 0 of the tensor instead and
+    // is replaced by zero when the segment is written to LDS, so all loads of a chunk are in
+    // flight together (and stay in flight while the previous chunk is being computed).
+    auto seg_row_valid = [&](int c0, int kk, int &ch, int &r, int &c, int &iy) -> bool {
+        const int seg = wave + NWAVE * kk;              // 0..47, uniform per wave
+        ch = seg / 6; r = seg - ch * 6;
+        c = c0 + ch; iy = y0 - 1 + r;
+        return pvalid && c < a.c_in && iy >= 0 && iy < a.h;
+    };
+    auto stage_load = [&](int c0, float (&t)[6][6]) {
 #pragma unroll
         for (int kk = 0; kk < 6; ++kk) {
-            const int seg = wave + NWAVE * kk;          // 0..47, uniform per wave
-            const int ch = seg / 6, r = seg - ch * 6;
-            const int c = c0 + ch, iy = y0 - 1 + r;
-            const bool rv = pvalid && c < a.c_in && iy >= 0 && iy < a.h;
+            int ch, r, c, iy;
+            const bool rv = seg_row_valid(c0, kk, ch, r, c, iy);
             if (VEC) {
-                // width is a multiple of 4 and the tensor 16-byte aligned: columns x0..x0+3 in one load
                 const size_t row_off = rv ? ((size_t(n) * a.c_in + c) * a.h + iy) * a.w + x0 : 0;
                 const float *rowp = reinterpret_cast<const float *>(x) + row_off;
                 const float4 mid = *reinterpret_cast<const float4 *>(rowp);
                 const bool lv = rv && x0 > 0, hv = rv && x0 + 4 < a.w;
-                const float lo = *(lv ? rowp - 1 : rowp);
-                const float hi = *(hv ? rowp + 4 : rowp);
-                v[kk][0] = lv ? lo : 0.0f;
-                v[kk][1] = rv ? mid.x : 0.0f; v[kk][2] = rv ? mid.y : 0.0f;
-                v[kk][3] = rv ? mid.z : 0.0f; v[kk][4] = rv ? mid.w : 0.0f;
-                v[kk][5] = hv ? hi : 0.0f;
+                t[kk][0] = *(lv ? rowp - 1 : rowp);
+                t[kk][1] = mid.x; t[kk][2] = mid.y; t[kk][3] = mid.z; t[kk][4] = mid.w;
+                t[kk][5] = *(hv ? rowp + 4 : rowp);
             } else {
 #pragma unroll
                 for (int cc = 0; cc < 6; ++cc) {
                     const int ix = x0 - 1 + cc;
                     const bool ok = rv && ix >= 0 && ix < a.w;
-                    const float t = ld_act(x, ok ? act_at<T, LAYOUT>(n, c, iy, ix, a.c_in, a.h, a.w) : size_t(0));
-                    v[kk][cc] = ok ? t : 0.0f;
+                    t[kk][cc] = ld_act(x, ok ? act_at<T, LAYOUT>(n, c, iy, ix, a.c_in, a.h, a.w) : size_t(0));
                 }
             }
         }
+    };
+    auto stage_store = [&](int c0, float *buf, const float (&t)[6][6]) {
 #pragma unroll
         for (int kk = 0; kk < 6; ++kk) {
-            const int seg = wave + NWAVE * kk;
-            const int ch = seg / 6, r = seg - ch * 6;
+            int ch, r, c, iy;
+            const bool rv = seg_row_valid(c0, kk, ch, r, c, iy);
+            float v[6];
+#pragma unroll
+            for (int cc = 0; cc < 6; ++cc) {
+                const int ix = x0 - 1 + cc;
+                v[cc] = (rv && ix >= 0 && ix < a.w) ? t[kk][cc] : 0.0f;
+            }
             float *dst = buf + (ch * 6 + r) * ROW_FLOATS;
-            *reinterpret_cast<float4 *>(dst + lane * 4) = make_float4(v[kk][0], v[kk][1], v[kk][2], v[kk][3]);
-            *reinterpret_cast<float2 *>(dst + 256 + lane * 2) = make_float2(v[kk][4], v[kk][5]);
+            *reinterpret_cast<float4 *>(dst + lane * 4) = make_float4(v[0], v[1], v[2], v[3]);
+            *reinterpret_cast<float2 *>(dst + 256 + lane * 2) = make_float2(v[4], v[5]);
         }
-        __syncthreads();
+    };
+    // This wave's records of a chunk are contiguous; each lane fetches one of them.  The chunk
+    // boundaries (chan_ptr at multiples of CH) of up to 64 consecutive chunks sit one per lane in
+    // chunk_ptrs and are read with v_readlane, so that no load has to be waited for here.
+    const int n_chunks = (a.c_in + CH - 1) / CH;
+    const uint32_t *__restrict__ ptr_row = a.chan_ptr + size_t(active ? fblk : 0) * a.row_len;
+    int win_base = 0;
+    uint32_t chunk_ptrs = ptr_row[min(lane, n_chunks) * CH];
+    auto fetch_records = [&](int chunk, uint32_t &k0, uint32_t &k_cnt, uint32_t &rec_m, float4 &rec_w) {
+        if (chunk + 1 - win_base > 63) {                 // every 63 chunks: next window
+            win_base = chunk;
+            chunk_ptrs = ptr_row[min(win_base + lane, n_chunks) * CH];
+            __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0), see the note in the record loop
+        }
+        k0 = __builtin_amdgcn_readlane(chunk_ptrs, chunk - win_base);
+        k_cnt = active ? __builtin_amdgcn_readlane(chunk_ptrs, chunk + 1 - win_base) - k0 : 0u;
+        const uint32_t idx = k0 + min(uint32_t(lane), k_cnt);   // k0 + k_cnt is the next record or the pad
+        rec_m = a.meta[idx];
+        rec_w = a.w4[idx];
+    };
+
+    float t[6][6];
+    uint32_t k0, k_cnt, rec_m;
+    float4 rec_w;
+    fetch_records(0, k0, k_cnt, rec_m, rec_w);
+    stage_load(0, t);
+    stage_store(0, lds, t);
+    __syncthreads();
+
+    for (int chunk = 0; chunk < n_chunks; ++chunk) {
+        const int c0 = chunk * CH;
+        const bool more = chunk + 1 < n_chunks;
+        const bool do_stage = more && !((a.dbg & 1) && chunk >= 2);
+        uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
+        float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
+        // next chunk: global loads are issued now and land while this chunk is computed (the
+        // record fetch comes first: it waits for its two pointers, which must not be behind the
+        // staging loads in the in-order load counter)
+        if (more) fetch_records(chunk + 1, nk0, nk_cnt, nrec_m, nrec_w);
+        if (do_stage) stage_load(c0 + CH, t);
 
         // ---- compute: records of this wave's filter block for channels c0 .. c0+7 ----
-        if (active) {
-            const uint32_t *__restrict__ cp = a.chan_ptr + size_t(fblk) * a.row_len + c0;
-            for (int ch = 0; ch < CH; ++ch) {
-                const uint32_t beg = cp[ch], end = cp[ch + 1];
-                if (beg == end) continue;
-                float in[36];
-                const float *src = buf + ch * CHAN_FLOATS;
-#pragma unroll
-                for (int r = 0; r < 6; ++r) {
-                    const float4 va = *reinterpret_cast<const float4 *>(src + r * ROW_FLOATS + lane * 4);
-                    const float2 vb = *reinterpret_cast<const float2 *>(src + r * ROW_FLOATS + 256 + lane * 2);
-                    in[r * 6 + 0] = va.x; in[r * 6 + 1] = va.y; in[r * 6 + 2] = va.z; in[r * 6 + 3] = va.w;
-                    in[r * 6 + 4] = vb.x; in[r * 6 + 5] = vb.y;
+        // Record j is broadcast from lane j with v_readlane; a record either starts a new channel
+        // (the lane reloads its 6x6 input neighbourhood from LDS) or reuses the registers; then
+        // its (slot, code) body runs: 16 FMAs per kept tap, weights in scalar registers.
+        if (active && !(a.dbg & 2)) {
+            const uint32_t buf_bytes = uint32_t(chunk & 1) * uint32_t(BUF_FLOATS * sizeof(float));
+            const uint32_t va = lane_a + buf_bytes, vb = lane_b + buf_bytes;
+            for (uint32_t base = 0; base < k_cnt; base += 64) {
+                if (base > 0) {
+                    const uint32_t idx = k0 + min(base + uint32_t(lane), k_cnt - 1);
+                    rec_m = a.meta[idx];
+                    rec_w = a.w4[idx];
+                    // Rare path (more than 64 records in one chunk).  Waiting here keeps the
+                    // record loop free of any wait on vector-memory loads, which would also wait
+                    // for the next chunk's staging loads issued above.
+                    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+                    if (lane == 0) rec_m |= kMetaFirstOfChannel;   // input registers do not survive between batches
                 }
-                for (uint32_t k = beg; k < end; ++k) {
-                    const uint32_t m = a.meta[k];
-                    const float4 wv = a.w4[k];
-                    switch (m) {
-                        PCONV_SLOT_CASES(0) PCONV_SLOT_CASES(1) PCONV_SLOT_CASES(2) PCONV_SLOT_CASES(3)
-                        PCONV_SLOT_CASES(4) PCONV_SLOT_CASES(5) PCONV_SLOT_CASES(6) PCONV_SLOT_CASES(7)
-                        default: break;
-                    }
-                }
+                const uint32_t nb = __builtin_amdgcn_readfirstlane(min(64u, k_cnt - base));
+                asm volatile(
+#include "pconv_tiled_compute.inc"
+                    : "+{v[128:143]}"(acc[0]), "+{v[144:159]}"(acc[1]), "+{v[160:175]}"(acc[2]),
+                      "+{v[176:191]}"(acc[3]), "+{v[192:207]}"(acc[4]), "+{v[208:223]}"(acc[5]),
+                      "+{v[224:239]}"(acc[6]), "+{v[240:255]}"(acc[7])
+                    : [recm] "v"(rec_m), [rw0] "v"(rec_w.x), [rw1] "v"(rec_w.y), [rw2] "v"(rec_w.z),
+                      [rw3] "v"(rec_w.w), [va] "v"(va), [vb] "v"(vb), [cnt] "s"(nb)
+                    : "v86", "v87", "v88", "v89", "v90", "v91", "v92", "v93", "v94", "v95", "v96", "v97", "v98", "v99", "v100", "v101",
+                      "v102", "v103", "v104", "v105", "v106", "v107", "v108", "v109", "v110", "v111",
+                      "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121",
+                      "v122", "v123", "v124", "v125", "v126", "v127",
+                      "s84", "s85", "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95",
+                      "scc", "memory");
             }
         }
-        // The next chunk is staged into the other buffer; the barrier after that staging also
-        // orders this chunk's reads before the buffer is overwritten two chunks from now.
+
+        // next chunk goes to the other buffer: nobody reads it any more (all waves passed the
+        // previous barrier after finishing the chunk before this one)
+        if (do_stage) stage_store(c0 + CH, lds + ((chunk + 1) & 1) * BUF_FLOATS, t);
+        k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m; rec_w = nrec_w;
+        __syncthreads();
     }
 
     // ---- epilogue: bias, ReLU, store (filters go back to their original index) ----
@@ -255,6 +285,7 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     a.n_blocks = h->tiled.num_blocks;
     a.n_groups = (a.n_blocks + NWAVE - 1) / NWAVE;
     a.relu = relu;
+    { const char *e = getenv("PCONV_DEBUG_FLAGS"); a.dbg = e ? atoi(e) : 0; }
     const bool vec = dtype == PCONV_F32 && layout == PCONV_NCHW && (win % 4 == 0) &&
                      (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
     const int64_t wgs = int64_t((a.n_tiles + 7) / 8) * 8 * a.n_groups;

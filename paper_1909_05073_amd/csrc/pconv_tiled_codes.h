@@ -20,6 +20,11 @@ constexpr uint16_t kCodeMask[kNumCodes] = {
     0x001, 0x002, 0x004, 0x008, 0x010, 0x020, 0x040, 0x080, 0x100,
 };
 
+// Record word of the tiled stream: bits 0-7 slot * kNumCodes + code, bits 8-10 channel within
+// its chunk, bit 11 set on the first record of a channel (the lane then reloads its input patch).
+constexpr uint32_t kMetaCaseMask = 0xFFu;
+constexpr uint32_t kMetaFirstOfChannel = 0x800u;
+
 constexpr int kTileFB = 8;      // filters per wave ("slots")
 constexpr int kTileWaves = 8;   // waves per workgroup
 constexpr int kTileCH = 8;      // input channels staged per LDS chunk
