@@ -1,17 +1,22 @@
 // Register-tiled PCONV kernel for gfx950 (stride 1).
 //
-// Work decomposition.  A workgroup of 8 waves owns 64 "patches" (each a 4x4 block of output
-// pixels of one image, one patch per lane) and 64 filters (8 per wave).  The input channels are
-// walked in chunks of 8: all 512 threads stage the 6x6 input neighbourhood of every patch of the
-// chunk's channels into LDS (zero-filled outside the image, so the inner loops have no bounds
-// tests), then every wave walks the records of its 8 filters for those channels.  For one input
-// channel a lane reads its 6x6 neighbourhood from LDS once (six b128 + six b64 reads) and keeps it
-// in registers for all of the wave's filters that are connected to that channel; each record then
-// costs 16 FMAs per kept tap on 128 accumulator registers, with the weights in scalar registers.
+// Work decomposition.  A workgroup of 8 waves owns 64 "patches" (a patch = a 4x4 block of output
+// pixels of one image; one patch per lane) and 32 filters (4 per wave, its "slots").  Two
+// workgroups share a compute unit, i.e. 4 waves per SIMD: a single wave issues a vector
+// instruction only about every 6.5 cycles, so it takes three to four of them to keep a SIMD busy.
 //
-// The pattern of a kernel selects straight-line code: the switch below has one case per
-// (slot, code), all register indices are compile-time constants (paper: per-pattern generated
-// code, branch per kernel instead of per weight; here by template instantiation).
+// The input channels are walked in chunks of 8.  For a chunk, all 512 threads stage the 6x6 input
+// neighbourhood of every patch into LDS (zero-filled outside the image, so the inner loops have no
+// bounds tests), and every wave copies the weights of its records for the chunk into its own LDS
+// block.  Then each wave walks its records: a record is one (kernel, code) pair, i.e. up to four
+// kept taps of one 3x3 kernel of one of the wave's filters.  When a record starts a new input
+// channel the lane reloads its 6x6 neighbourhood from LDS (six b128 + six b64 reads) and keeps it
+// in registers for all of the wave's filters connected to that channel; the record itself costs
+// 16 FMAs per kept tap on the slot's 16 accumulator registers.
+//
+// The record loop is generated assembly (gen_tiled_compute.py): the pattern of a kernel selects
+// straight-line code with compile-time register indices (paper: per-pattern generated code, one
+// branch per kernel instead of per weight), reached by one computed jump per record.
 #include <hip/hip_runtime.h>
 #include <cstdlib>
 
@@ -24,10 +29,16 @@ namespace {
 
 struct bf16_t { uint16_t bits; };
 
-constexpr int FB = kTileFB, NWAVE = kTileWaves, CH = kTileCH;
-constexpr int ROW_FLOATS = 64 * 6;            // one input row of all 64 patches: [64][4] then [64][2]
+constexpr int FB = kTileFB, NWAVE = kTileWaves, CH = kTileCH, BATCH = kTileBatch;
+constexpr int ROW_FLOATS = 64 * 6;            // one input row of all 64 patches: columns x0..x0+3 as [64][4],
+                                              // then column x0-1 as [64], then column x0+4 as [64]
 constexpr int CHAN_FLOATS = 6 * ROW_FLOATS;   // 2304
-constexpr int BUF_FLOATS = CH * CHAN_FLOATS;  // 18432 floats = 72 KiB; two buffers
+constexpr int BUF_FLOATS = CH * CHAN_FLOATS;  // 18432 floats = 72 KiB
+constexpr int WLDS_FLOATS = NWAVE * BATCH * 4;                       // weight blocks of the 8 waves
+constexpr size_t LDS_BYTES = size_t(BUF_FLOATS + WLDS_FLOATS) * 4;   // 77824: two workgroups per CU
+
+static_assert(kNumCodes == 24 && FB == 4 && CH == 8 && BATCH == 32,
+              "gen_tiled_compute.py is written for 24 codes, 4 slots, 8-channel chunks, 32-record batches");
 
 __device__ __forceinline__ float ld_act(const float *p, size_t i) { return p[i]; }
 __device__ __forceinline__ float ld_act(const bf16_t *p, size_t i) { return __uint_as_float(uint32_t(p[i].bits) << 16); }
@@ -40,8 +51,6 @@ __device__ __forceinline__ void st_act(bf16_t *p, size_t i, float v)
 }
 
 typedef float v16f __attribute__((ext_vector_type(16)));
-
-static_assert(kNumCodes == 24 && FB == 8 && CH == 8, "gen_tiled_compute.py is written for 24 codes, 8 slots, 8-channel chunks");
 
 struct TiledArgs {
     const void *x; void *y; const float *bias;
@@ -62,7 +71,7 @@ __device__ __forceinline__ size_t act_at(int n, int c, int y, int x, int C, int 
 // VEC: fp32 NCHW tensors whose width is a multiple of 4 and whose base is 16-byte aligned move
 // the four centre columns of a row (and the four outputs of a row) with one 128-bit access.
 template <typename T, int LAYOUT, bool VEC>
-__global__ void __launch_bounds__(512)
+__global__ void __launch_bounds__(512, 4)   // 4 waves per SIMD: at most 128 VGPRs
 conv_tiled_kernel(const TiledArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -90,148 +99,168 @@ conv_tiled_kernel(const TiledArgs a)
     const int y0 = (prem / a.px) * 4, x0 = (prem % a.px) * 4;
 
     // accumulators: slot s, output (row i, column k) of the patch = acc[s][4 * i + k].  The record
-    // loop below is assembly with a fixed register map, so each vector is pinned to its registers.
+    // loop is assembly with a fixed register map, so each vector is pinned to its registers there.
     v16f acc[FB];
 #pragma unroll
     for (int s = 0; s < FB; ++s) acc[s] = 0.0f;
-    // per-lane LDS byte addresses of this lane's patch inside a staged buffer (128-bit / 64-bit part)
+    // per-lane LDS byte addresses: the lane's patch in the staged buffer (the four centre columns of a
+    // row / its two halo columns), and this wave's weight block
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
-    const uint32_t lane_a = lds_base + uint32_t(lane) * 16u;
-    const uint32_t lane_b = lds_base + 1024u + uint32_t(lane) * 8u;
+    const uint32_t va = lds_base + uint32_t(lane) * 16u;
+    const uint32_t vb = lds_base + 1024u + uint32_t(lane) * 4u;
+    float *wlds = lds + BUF_FLOATS + wave * (BATCH * 4);
+    const uint32_t wa = lds_base + uint32_t(BUF_FLOATS + wave * (BATCH * 4)) * 4u;
 
     // ---- staging helpers: every thread owns 6 (channel, row) segments of its lane's patch ----
     // Loads are branch-free: an out-of-image element reads element 0 of the tensor instead and
     // is replaced by zero when the segment is written to LDS, so all loads of a chunk are in
-    // flight together (and stay in flight while the previous chunk is being computed).
-    auto seg_row_valid = [&](int c0, int kk, int &ch, int &r, int &c, int &iy) -> bool {
-        const int seg = wave + NWAVE * kk;              // 0..47, uniform per wave
-        ch = seg / 6; r = seg - ch * 6;
-        c = c0 + ch; iy = y0 - 1 + r;
-        return pvalid && c < a.c_in && iy >= 0 && iy < a.h;
-    };
-    auto stage_load = [&](int c0, float (&t)[6][6]) {
+    // flight together.  What is valid for this lane does not change from chunk to chunk and is
+    // kept as one bit mask: bits 0-5 input rows y0-1 .. y0+4, bits 8-13 input columns x0-1 .. x0+4.
+    uint32_t vmask = 0;
+#pragma unroll
+    for (int r = 0; r < 6; ++r) {
+        const int iy = y0 - 1 + r, ix = x0 - 1 + r;
+        if (pvalid && iy >= 0 && iy < a.h) vmask |= 1u << r;
+        if (ix >= 0 && ix < a.w) vmask |= 0x100u << r;
+    }
+    const int hw = a.h * a.w;
+    // element offset of (channel 0 of the chunk, row y0-1, column x0) follows from c0; tensors have
+    // fewer than 2^31 elements, so 32-bit offsets suffice (they are only used where valid)
+    const int lane_off = LAYOUT == PCONV_NCHW ? (n * a.c_in * a.h + (y0 - 1)) * a.w + x0
+                                              : ((n * a.h + (y0 - 1)) * a.w + x0) * a.c_in;
+    typedef __attribute__((address_space(3))) void *lds_ptr_t;
+    typedef const __attribute__((address_space(1))) void *glb_ptr_t;
+    // VEC path: global -> LDS directly, no registers and no vector ALU work.  Lanes whose row (or
+    // halo column) lies outside the image are masked off; their LDS words were zeroed once at
+    // kernel start and are never written, so they stay zero for every chunk.
+    auto stage_direct = [&](int c0) {
+        int lane_off_now = lane_off;
+        asm volatile("" : "+v"(lane_off_now));           // keeps the per-lane part of the address one register
+        const float *xf = reinterpret_cast<const float *>(x);
 #pragma unroll
         for (int kk = 0; kk < 6; ++kk) {
-            int ch, r, c, iy;
-            const bool rv = seg_row_valid(c0, kk, ch, r, c, iy);
-            if (VEC) {
-                const size_t row_off = rv ? ((size_t(n) * a.c_in + c) * a.h + iy) * a.w + x0 : 0;
-                const float *rowp = reinterpret_cast<const float *>(x) + row_off;
-                const float4 mid = *reinterpret_cast<const float4 *>(rowp);
-                const bool lv = rv && x0 > 0, hv = rv && x0 + 4 < a.w;
-                t[kk][0] = *(lv ? rowp - 1 : rowp);
-                t[kk][1] = mid.x; t[kk][2] = mid.y; t[kk][3] = mid.z; t[kk][4] = mid.w;
-                t[kk][5] = *(hv ? rowp + 4 : rowp);
-            } else {
-#pragma unroll
-                for (int cc = 0; cc < 6; ++cc) {
-                    const int ix = x0 - 1 + cc;
-                    const bool ok = rv && ix >= 0 && ix < a.w;
-                    t[kk][cc] = ld_act(x, ok ? act_at<T, LAYOUT>(n, c, iy, ix, a.c_in, a.h, a.w) : size_t(0));
-                }
-            }
+            const int seg = wave + NWAVE * kk;           // 0..47, uniform per wave
+            const int ch = seg / 6, r = seg - ch * 6;
+            const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
+            const float *src = xf + (lane_off_now + (c0 + ch) * hw + r * a.w);
+            float *dst = lds + (ch * 6 + r) * ROW_FLOATS;
+            if (rv) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
+            if (rv && (vmask & 0x100u)) __builtin_amdgcn_global_load_lds((glb_ptr_t)(src - 1), (lds_ptr_t)(dst + 256), 4, 0, 0);
+            if (rv && (vmask & 0x2000u)) __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + 4), (lds_ptr_t)(dst + 320), 4, 0, 0);
         }
     };
-    auto stage_store = [&](int c0, float *buf, const float (&t)[6][6]) {
+    // generic path (any layout / dtype / width): through registers, with conversion to fp32
+    auto stage_load = [&](int c0, float (&t)[6][6]) {
+        int lane_off_now = lane_off;
+        asm volatile("" : "+v"(lane_off_now));
 #pragma unroll
         for (int kk = 0; kk < 6; ++kk) {
-            int ch, r, c, iy;
-            const bool rv = seg_row_valid(c0, kk, ch, r, c, iy);
-            float v[6];
+            const int seg = wave + NWAVE * kk;
+            const int ch = seg / 6, r = seg - ch * 6;
+            const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
+            const int off = LAYOUT == PCONV_NCHW ? lane_off_now + (c0 + ch) * hw + r * a.w
+                                                 : lane_off_now + r * a.w * a.c_in + (c0 + ch);
 #pragma unroll
             for (int cc = 0; cc < 6; ++cc) {
-                const int ix = x0 - 1 + cc;
-                v[cc] = (rv && ix >= 0 && ix < a.w) ? t[kk][cc] : 0.0f;
+                const bool ok = rv && ((vmask >> (8 + cc)) & 1u);
+                const int e = LAYOUT == PCONV_NCHW ? off + (cc - 1) : off + (cc - 1) * a.c_in;
+                t[kk][cc] = ld_act(x, size_t(ok ? e : 0));
             }
-            float *dst = buf + (ch * 6 + r) * ROW_FLOATS;
-            *reinterpret_cast<float4 *>(dst + lane * 4) = make_float4(v[0], v[1], v[2], v[3]);
-            *reinterpret_cast<float2 *>(dst + 256 + lane * 2) = make_float2(v[4], v[5]);
         }
     };
-    // This wave's records of a chunk are contiguous; each lane fetches one of them.  The chunk
-    // boundaries (chan_ptr at multiples of CH) of up to 64 consecutive chunks sit one per lane in
-    // chunk_ptrs and are read with v_readlane, so that no load has to be waited for here.
+    auto stage_store = [&](int c0, const float (&t)[6][6]) {
+#pragma unroll
+        for (int kk = 0; kk < 6; ++kk) {
+            const int seg = wave + NWAVE * kk;
+            const int ch = seg / 6, r = seg - ch * 6;
+            const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
+            float v[6];
+#pragma unroll
+            for (int cc = 0; cc < 6; ++cc) v[cc] = (rv && ((vmask >> (8 + cc)) & 1u)) ? t[kk][cc] : 0.0f;
+            float *dst = lds + (ch * 6 + r) * ROW_FLOATS;
+            *reinterpret_cast<float4 *>(dst + lane * 4) = make_float4(v[1], v[2], v[3], v[4]);
+            dst[256 + lane] = v[0];
+            dst[320 + lane] = v[5];
+        }
+    };
+
+    if (VEC) {
+        // zero the staged buffer once (see stage_direct)
+#pragma unroll
+        for (int j = 0; j < BUF_FLOATS / (512 * 4); ++j)
+            *reinterpret_cast<float4 *>(lds + (j * 512 + threadIdx.x) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+
+    // The records of a (filter block, chunk) are contiguous.  The chunk boundaries (chan_ptr at
+    // multiples of CH) of up to 64 consecutive chunks sit one per lane in chunk_ptrs and are read
+    // with v_readlane.
     const int n_chunks = (a.c_in + CH - 1) / CH;
     const uint32_t *__restrict__ ptr_row = a.chan_ptr + size_t(active ? fblk : 0) * a.row_len;
     int win_base = 0;
     uint32_t chunk_ptrs = ptr_row[min(lane, n_chunks) * CH];
-    auto fetch_records = [&](int chunk, uint32_t &k0, uint32_t &k_cnt, uint32_t &rec_m, float4 &rec_w) {
-        if (chunk + 1 - win_base > 63) {                 // every 63 chunks: next window
-            win_base = chunk;
-            chunk_ptrs = ptr_row[min(win_base + lane, n_chunks) * CH];
-            __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0), see the note in the record loop
-        }
-        k0 = __builtin_amdgcn_readlane(chunk_ptrs, chunk - win_base);
-        k_cnt = active ? __builtin_amdgcn_readlane(chunk_ptrs, chunk + 1 - win_base) - k0 : 0u;
-        const uint32_t idx = k0 + min(uint32_t(lane), k_cnt);   // k0 + k_cnt is the next record or the pad
-        rec_m = a.meta[idx];
-        rec_w = a.w4[idx];
-    };
-
-    float t[6][6];
-    uint32_t k0, k_cnt, rec_m;
-    float4 rec_w;
-    fetch_records(0, k0, k_cnt, rec_m, rec_w);
-    stage_load(0, t);
-    stage_store(0, lds, t);
-    __syncthreads();
 
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
         const int c0 = chunk * CH;
-        const bool more = chunk + 1 < n_chunks;
-        const bool do_stage = more && !((a.dbg & 1) && chunk >= 2);
-        uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
-        float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
-        // next chunk: global loads are issued now and land while this chunk is computed (the
-        // record fetch comes first: it waits for its two pointers, which must not be behind the
-        // staging loads in the in-order load counter)
-        if (more) fetch_records(chunk + 1, nk0, nk_cnt, nrec_m, nrec_w);
-        if (do_stage) stage_load(c0 + CH, t);
+        if (chunk + 1 - win_base > 63) {                 // every 63 chunks: next window of boundaries
+            win_base = chunk;
+            chunk_ptrs = ptr_row[min(win_base + lane, n_chunks) * CH];
+        }
+        const uint32_t k0 = __builtin_amdgcn_readlane(chunk_ptrs, chunk - win_base);
+        const uint32_t k_cnt = active ? __builtin_amdgcn_readlane(chunk_ptrs, chunk + 1 - win_base) - k0 : 0u;
+        // first batch of this wave's records: lane j holds record j (k0 + k_cnt is the next
+        // record or the padding record, always readable)
+        uint32_t ridx = k0 + min(uint32_t(lane), k_cnt);
+        uint32_t rec_m = a.meta[ridx];
+        float4 rec_w = a.w4[ridx];
 
-        // ---- compute: records of this wave's filter block for channels c0 .. c0+7 ----
-        // Record j is broadcast from lane j with v_readlane; a record either starts a new channel
-        // (the lane reloads its 6x6 input neighbourhood from LDS) or reuses the registers; then
-        // its (slot, code) body runs: 16 FMAs per kept tap, weights in scalar registers.
-        if (active && !(a.dbg & 2)) {
-            const uint32_t buf_bytes = uint32_t(chunk & 1) * uint32_t(BUF_FLOATS * sizeof(float));
-            const uint32_t va = lane_a + buf_bytes, vb = lane_b + buf_bytes;
-            for (uint32_t base = 0; base < k_cnt; base += 64) {
-                if (base > 0) {
-                    const uint32_t idx = k0 + min(base + uint32_t(lane), k_cnt - 1);
-                    rec_m = a.meta[idx];
-                    rec_w = a.w4[idx];
-                    // Rare path (more than 64 records in one chunk).  Waiting here keeps the
-                    // record loop free of any wait on vector-memory loads, which would also wait
-                    // for the next chunk's staging loads issued above.
-                    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-                    if (lane == 0) rec_m |= kMetaFirstOfChannel;   // input registers do not survive between batches
-                }
-                const uint32_t nb = __builtin_amdgcn_readfirstlane(min(64u, k_cnt - base));
-                asm volatile(
-#include "pconv_tiled_compute.inc"
-                    : "+{v[128:143]}"(acc[0]), "+{v[144:159]}"(acc[1]), "+{v[160:175]}"(acc[2]),
-                      "+{v[176:191]}"(acc[3]), "+{v[192:207]}"(acc[4]), "+{v[208:223]}"(acc[5]),
-                      "+{v[224:239]}"(acc[6]), "+{v[240:255]}"(acc[7])
-                    : [recm] "v"(rec_m), [rw0] "v"(rec_w.x), [rw1] "v"(rec_w.y), [rw2] "v"(rec_w.z),
-                      [rw3] "v"(rec_w.w), [va] "v"(va), [vb] "v"(vb), [cnt] "s"(nb)
-                    : "v86", "v87", "v88", "v89", "v90", "v91", "v92", "v93", "v94", "v95", "v96", "v97", "v98", "v99", "v100", "v101",
-                      "v102", "v103", "v104", "v105", "v106", "v107", "v108", "v109", "v110", "v111",
-                      "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121",
-                      "v122", "v123", "v124", "v125", "v126", "v127",
-                      "s84", "s85", "s86", "s87", "s88", "s89", "s90", "s91", "s92", "s93", "s94", "s95",
-                      "scc", "memory");
+        const bool do_stage = !((a.dbg & 1) && chunk >= 1);
+        __syncthreads();                                 // every wave is done reading the previous chunk
+        if (do_stage) {
+            // the loads' latency is covered by the other workgroup of this compute unit
+            if (VEC) {
+                stage_direct(c0);
+            } else {
+                float t[6][6];
+                stage_load(c0, t);
+                stage_store(c0, t);
             }
         }
-
-        // next chunk goes to the other buffer: nobody reads it any more (all waves passed the
-        // previous barrier after finishing the chunk before this one)
-        if (do_stage) stage_store(c0 + CH, lds + ((chunk + 1) & 1) * BUF_FLOATS, t);
-        k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m; rec_w = nrec_w;
+        if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
         __syncthreads();
+
+        if (active && !(a.dbg & 2)) {
+            for (uint32_t base = 0; base < k_cnt; base += BATCH) {
+                if (base > 0) {
+                    // more than BATCH records in this chunk: next batch (the wave's weight block
+                    // is private, and LDS accesses of one wave execute in order)
+                    ridx = k0 + min(base + uint32_t(lane), k_cnt);
+                    rec_m = a.meta[ridx];
+                    rec_w = a.w4[ridx];
+                    if (lane == 0) rec_m |= kMetaFirstOfChannel;   // input registers do not survive between batches
+                    if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
+                }
+                const uint32_t nb = __builtin_amdgcn_readfirstlane(min(uint32_t(BATCH), k_cnt - base));
+                asm volatile(
+#include "pconv_tiled_compute.inc"
+                    : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
+                    : [recm] "v"(rec_m), [va] "v"(va), [vb] "v"(vb), [wa] "s"(wa), [cnt] "s"(nb)
+                    : "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
+                      "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45",
+                      "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57",
+                      "v58", "v59", "v60", "v61", "v62", "v63",
+                      "s84", "s85", "s90", "s91", "s92", "s93", "s94", "s95", "scc", "memory");
+            }
+        }
     }
 
     // ---- epilogue: bias, ReLU, store (filters go back to their original index) ----
-    if (!active || !pvalid) return;
+    if (!active) return;
+    // the patch coordinates are recomputed here instead of being kept in registers across the loop
+    int pidx_e = tile * 64 + lane;
+    asm volatile("" : "+v"(pidx_e));
+    if (pidx_e >= a.n_patches) return;
+    const int n_e = pidx_e / per_img, prem_e = pidx_e - n_e * per_img;
+    const int ye = (prem_e / a.px) * 4, xe = (prem_e % a.px) * 4;
     const int ho = a.h, wo = a.w;
 #pragma unroll
     for (int s = 0; s < FB; ++s) {
@@ -240,7 +269,7 @@ conv_tiled_kernel(const TiledArgs a)
         const float b = a.bias ? a.bias[f] : 0.0f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int oy = y0 + i;
+            const int oy = ye + i;
             if (oy >= ho) continue;
             float o[4];
 #pragma unroll
@@ -249,12 +278,12 @@ conv_tiled_kernel(const TiledArgs a)
                 if (a.relu) o[k] = fmaxf(o[k], 0.0f);
             }
             if (VEC) {
-                float *dst = reinterpret_cast<float *>(y) + ((size_t(n) * a.c_out + f) * ho + oy) * wo + x0;
+                float *dst = reinterpret_cast<float *>(y) + ((size_t(n_e) * a.c_out + f) * ho + oy) * wo + xe;
                 *reinterpret_cast<float4 *>(dst) = make_float4(o[0], o[1], o[2], o[3]);
             } else {
 #pragma unroll
                 for (int k = 0; k < 4; ++k)
-                    if (x0 + k < wo) st_act(y, act_at<T, LAYOUT>(n, f, oy, x0 + k, a.c_out, ho, wo), o[k]);
+                    if (xe + k < wo) st_act(y, act_at<T, LAYOUT>(n_e, f, oy, xe + k, a.c_out, ho, wo), o[k]);
             }
         }
     }
@@ -264,7 +293,7 @@ conv_tiled_kernel(const TiledArgs a)
 
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype)
 {
-    (void)n; (void)layout; (void)dtype;
+    (void)layout; (void)dtype;
     if (!h->d_meta || stride != 1) return false;
     const int64_t patches = int64_t(n) * ((hin + 3) / 4) * ((win + 3) / 4);
     return patches < (int64_t(1) << 30);
@@ -290,19 +319,18 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
                      (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
     const int64_t wgs = int64_t((a.n_tiles + 7) / 8) * 8 * a.n_groups;
     if (wgs > 0x7FFFFFFF) { set_error("pconv_conv2d: too many workgroups"); return PCONV_UNSUPPORTED; }
-    const size_t lds_bytes = size_t(2) * BUF_FLOATS * sizeof(float);
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
 #define PCONV_LAUNCH(T, L, V)                                                                          \
     do {                                                                                              \
         static bool attr_done = false;                                                                \
         if (!attr_done) {                                                                             \
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_tiled_kernel<T, L, V>),         \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));      \
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_tiled_kernel<T, L, V>),      \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(LDS_BYTES));      \
             attr_done = (e == hipSuccess);                                                            \
         }                                                                                             \
         if (e == hipSuccess)                                                                          \
-            hipLaunchKernelGGL((conv_tiled_kernel<T, L, V>), dim3(unsigned(wgs)), dim3(512), lds_bytes, st, a); \
+            hipLaunchKernelGGL((conv_tiled_kernel<T, L, V>), dim3(unsigned(wgs)), dim3(512), LDS_BYTES, st, a); \
     } while (0)
     if (vec) PCONV_LAUNCH(float, PCONV_NCHW, true);
     else if (dtype == PCONV_F32) {
