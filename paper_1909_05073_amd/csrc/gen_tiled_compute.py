@@ -21,7 +21,10 @@ addresses of the lane's patch in the staged buffer (the four centre columns of a
 halo columns, which sit 256 bytes apart), %[wa] LDS byte address
 of this wave's weight block (SGPR; 16 bytes per record), %[cnt] number of records (SGPR, 1..32).
 """
+import os
 import sys
+
+EXP = os.environ.get('PCONV_GEN_EXP', '')   # timing experiments only
 
 ACC, INP, WREG = 64, 28, 24
 STRIDE_LOG2 = 9
@@ -42,12 +45,19 @@ def fetch(lines):
         "v_readlane_b32 s85, %[recm], s84",
         "s_nop 0",
         "s_bitcmp1_b32 s85, 11",
-        "s_cbranch_scc1 PATCH_%=",
     ]
+    if 'nopatch' not in EXP:
+        lines.append("s_cbranch_scc1 PATCH_%=")
+    if 'noweights' in EXP:
+        lines.remove("ds_read_b128 v[%d:%d], v23" % (WREG, WREG + 3))
     jump(lines)
 
 
 def jump(lines):
+    if 'nojump' in EXP:
+        lines += ["s_and_b32 s90, s85, 0", "s_min_u32 s90, s90, 95", "s_lshl_b32 s90, s90, 9",
+                  "s_add_u32 s94, s92, s90", "s_addc_u32 s95, s93, 0", "s_branch TABLE_%="]
+        return
     lines += [
         "s_and_b32 s90, s85, 0xff",
         "s_min_u32 s90, s90, %d" % (SLOTS * len(CODE_MASKS) - 1),

@@ -1,14 +1,15 @@
 // Register-tiled PCONV kernel for gfx950 (stride 1).
 //
-// Work decomposition.  A workgroup of 8 waves owns 64 "patches" (a patch = a 4x4 block of output
-// pixels of one image; one patch per lane) and 32 filters (4 per wave, its "slots").  Two
-// workgroups share a compute unit, i.e. 4 waves per SIMD: a single wave issues a vector
+// Work decomposition.  A workgroup of 16 waves owns 64 "patches" (a patch = a 4x4 block of output
+// pixels of one image; one patch per lane) and 64 filters (4 per wave, its "slots").  One
+// workgroup fills a compute unit with 4 waves per SIMD: a single wave issues a vector
 // instruction only about every 6.5 cycles, so it takes three to four of them to keep a SIMD busy.
 //
-// The input channels are walked in chunks of 8.  For a chunk, all 512 threads stage the 6x6 input
-// neighbourhood of every patch into LDS (zero-filled outside the image, so the inner loops have no
-// bounds tests), and every wave copies the weights of its records for the chunk into its own LDS
-// block.  Then each wave walks its records: a record is one (kernel, code) pair, i.e. up to four
+// The input channels are walked in chunks of 8 through two LDS buffers.  For a chunk, all 1024
+// threads stage the 6x6 input neighbourhood of every patch into LDS (zero outside the image, so
+// the inner loops have no bounds tests) while the previous chunk is being computed, and every wave
+// copies the weights of its records for the chunk into its own LDS block.  Then each wave walks
+// its records: a record is one (kernel, code) pair, i.e. up to four
 // kept taps of one 3x3 kernel of one of the wave's filters.  When a record starts a new input
 // channel the lane reloads its 6x6 neighbourhood from LDS (six b128 + six b64 reads) and keeps it
 // in registers for all of the wave's filters connected to that channel; the record itself costs
@@ -34,8 +35,8 @@ constexpr int ROW_FLOATS = 64 * 6;            // one input row of all 64 patches
                                               // then column x0-1 as [64], then column x0+4 as [64]
 constexpr int CHAN_FLOATS = 6 * ROW_FLOATS;   // 2304
 constexpr int BUF_FLOATS = CH * CHAN_FLOATS;  // 18432 floats = 72 KiB
-constexpr int WLDS_FLOATS = NWAVE * BATCH * 4;                       // weight blocks of the 8 waves
-constexpr size_t LDS_BYTES = size_t(BUF_FLOATS + WLDS_FLOATS) * 4;   // 77824: two workgroups per CU
+constexpr int WLDS_FLOATS = NWAVE * BATCH * 4;                       // weight blocks of the 16 waves
+constexpr size_t LDS_BYTES = size_t(2 * BUF_FLOATS + WLDS_FLOATS) * 4;   // 155648 of the CU's 160 KiB
 
 static_assert(kNumCodes == 24 && FB == 4 && CH == 8 && BATCH == 32,
               "gen_tiled_compute.py is written for 24 codes, 4 slots, 8-channel chunks, 32-record batches");
@@ -71,7 +72,7 @@ __device__ __forceinline__ size_t act_at(int n, int c, int y, int x, int C, int 
 // VEC: fp32 NCHW tensors whose width is a multiple of 4 and whose base is 16-byte aligned move
 // the four centre columns of a row (and the four outputs of a row) with one 128-bit access.
 template <typename T, int LAYOUT, bool VEC>
-__global__ void __launch_bounds__(512, 4)   // 4 waves per SIMD: at most 128 VGPRs
+__global__ void __launch_bounds__(1024, 4)   // 4 waves per SIMD: at most 128 VGPRs
 conv_tiled_kernel(const TiledArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
@@ -108,8 +109,8 @@ conv_tiled_kernel(const TiledArgs a)
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
     const uint32_t va = lds_base + uint32_t(lane) * 16u;
     const uint32_t vb = lds_base + 1024u + uint32_t(lane) * 4u;
-    float *wlds = lds + BUF_FLOATS + wave * (BATCH * 4);
-    const uint32_t wa = lds_base + uint32_t(BUF_FLOATS + wave * (BATCH * 4)) * 4u;
+    float *wlds = lds + 2 * BUF_FLOATS + wave * (BATCH * 4);
+    const uint32_t wa = lds_base + uint32_t(2 * BUF_FLOATS + wave * (BATCH * 4)) * 4u;
 
     // ---- staging helpers: every thread owns 6 (channel, row) segments of its lane's patch ----
     // Loads are branch-free: an out-of-image element reads element 0 of the tensor instead and
@@ -128,33 +129,40 @@ conv_tiled_kernel(const TiledArgs a)
     // fewer than 2^31 elements, so 32-bit offsets suffice (they are only used where valid)
     const int lane_off = LAYOUT == PCONV_NCHW ? (n * a.c_in * a.h + (y0 - 1)) * a.w + x0
                                               : ((n * a.h + (y0 - 1)) * a.w + x0) * a.c_in;
-    typedef __attribute__((address_space(3))) void *lds_ptr_t;
-    typedef const __attribute__((address_space(1))) void *glb_ptr_t;
     // VEC path: global -> LDS directly, no registers and no vector ALU work.  Lanes whose row (or
     // halo column) lies outside the image are masked off; their LDS words were zeroed once at
     // kernel start and are never written, so they stay zero for every chunk.
-    auto stage_direct = [&](int c0) {
+    constexpr int SEGS = 48 / NWAVE;                     // (channel, row) segments per wave and chunk
+    auto stage_direct = [&](int c0, float *buf) {
         int lane_off_now = lane_off;
         asm volatile("" : "+v"(lane_off_now));           // keeps the per-lane part of the address one register
         const float *xf = reinterpret_cast<const float *>(x);
 #pragma unroll
-        for (int kk = 0; kk < 6; ++kk) {
+        for (int kk = 0; kk < SEGS; ++kk) {
             const int seg = wave + NWAVE * kk;           // 0..47, uniform per wave
             const int ch = seg / 6, r = seg - ch * 6;
             const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
             const float *src = xf + (lane_off_now + (c0 + ch) * hw + r * a.w);
-            float *dst = lds + (ch * 6 + r) * ROW_FLOATS;
-            if (rv) __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)dst, 16, 0, 0);
-            if (rv && (vmask & 0x100u)) __builtin_amdgcn_global_load_lds((glb_ptr_t)(src - 1), (lds_ptr_t)(dst + 256), 4, 0, 0);
-            if (rv && (vmask & 0x2000u)) __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + 4), (lds_ptr_t)(dst + 320), 4, 0, 0);
+            float *dst = buf + (ch * 6 + r) * ROW_FLOATS;
+            // LDS address of lane 0's element goes to M0; every lane adds lane * size, and the
+            // instruction's immediate offset applies to the LDS address as well as to the global
+            // one (hence the +4 / -16 corrections for the two halo columns).  Written as
+            // assembly so that the compiler does not track these loads: it would otherwise wait for
+            // them before the record loop (they are waited for explicitly before the next barrier).
+            const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(dst));
+            if (rv) asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst_b));
+            if (rv && (vmask & 0x100u))
+                asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dword %0, off offset:-4" ::"v"(src), "s"(dst_b + 1024u + 4u));
+            if (rv && (vmask & 0x2000u))
+                asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dword %0, off offset:16" ::"v"(src), "s"(dst_b + 1280u - 16u));
         }
     };
     // generic path (any layout / dtype / width): through registers, with conversion to fp32
-    auto stage_load = [&](int c0, float (&t)[6][6]) {
+    auto stage_load = [&](int c0, float (&t)[SEGS][6]) {
         int lane_off_now = lane_off;
         asm volatile("" : "+v"(lane_off_now));
 #pragma unroll
-        for (int kk = 0; kk < 6; ++kk) {
+        for (int kk = 0; kk < SEGS; ++kk) {
             const int seg = wave + NWAVE * kk;
             const int ch = seg / 6, r = seg - ch * 6;
             const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
@@ -168,16 +176,16 @@ conv_tiled_kernel(const TiledArgs a)
             }
         }
     };
-    auto stage_store = [&](int c0, const float (&t)[6][6]) {
+    auto stage_store = [&](int c0, float *buf, const float (&t)[SEGS][6]) {
 #pragma unroll
-        for (int kk = 0; kk < 6; ++kk) {
+        for (int kk = 0; kk < SEGS; ++kk) {
             const int seg = wave + NWAVE * kk;
             const int ch = seg / 6, r = seg - ch * 6;
             const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
             float v[6];
 #pragma unroll
             for (int cc = 0; cc < 6; ++cc) v[cc] = (rv && ((vmask >> (8 + cc)) & 1u)) ? t[kk][cc] : 0.0f;
-            float *dst = lds + (ch * 6 + r) * ROW_FLOATS;
+            float *dst = buf + (ch * 6 + r) * ROW_FLOATS;
             *reinterpret_cast<float4 *>(dst + lane * 4) = make_float4(v[1], v[2], v[3], v[4]);
             dst[256 + lane] = v[0];
             dst[320 + lane] = v[5];
@@ -185,10 +193,11 @@ conv_tiled_kernel(const TiledArgs a)
     };
 
     if (VEC) {
-        // zero the staged buffer once (see stage_direct)
+        // zero both staged buffers once (see stage_direct)
 #pragma unroll
-        for (int j = 0; j < BUF_FLOATS / (512 * 4); ++j)
-            *reinterpret_cast<float4 *>(lds + (j * 512 + threadIdx.x) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < 2 * BUF_FLOATS / (NWAVE * 64 * 4); ++j)
+            *reinterpret_cast<float4 *>(lds + (j * NWAVE * 64 + threadIdx.x) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+        __syncthreads();
     }
 
     // The records of a (filter block, chunk) are contiguous.  The chunk boundaries (chan_ptr at
@@ -199,8 +208,19 @@ conv_tiled_kernel(const TiledArgs a)
     int win_base = 0;
     uint32_t chunk_ptrs = ptr_row[min(lane, n_chunks) * CH];
 
+    auto stage = [&](int chunk) {
+        float *buf = lds + (chunk & 1) * BUF_FLOATS;
+        if (VEC) {
+            stage_direct(chunk * CH, buf);
+        } else {
+            float t[SEGS][6];
+            stage_load(chunk * CH, t);
+            stage_store(chunk * CH, buf, t);
+        }
+    };
+    stage(0);
+
     for (int chunk = 0; chunk < n_chunks; ++chunk) {
-        const int c0 = chunk * CH;
         if (chunk + 1 - win_base > 63) {                 // every 63 chunks: next window of boundaries
             win_base = chunk;
             chunk_ptrs = ptr_row[min(win_base + lane, n_chunks) * CH];
@@ -212,23 +232,16 @@ conv_tiled_kernel(const TiledArgs a)
         uint32_t ridx = k0 + min(uint32_t(lane), k_cnt);
         uint32_t rec_m = a.meta[ridx];
         float4 rec_w = a.w4[ridx];
-
-        const bool do_stage = !((a.dbg & 1) && chunk >= 1);
-        __syncthreads();                                 // every wave is done reading the previous chunk
-        if (do_stage) {
-            // the loads' latency is covered by the other workgroup of this compute unit
-            if (VEC) {
-                stage_direct(c0);
-            } else {
-                float t[6][6];
-                stage_load(c0, t);
-                stage_store(c0, t);
-            }
-        }
         if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wave's staging loads have landed
+        // This chunk's inputs were requested one chunk ago; the barrier makes them (all loads are
+        // waited for before it) and the weights visible, and tells that every wave has finished
+        // the previous chunk, whose buffer is refilled right away for the next chunk.
         __syncthreads();
+        if (chunk + 1 < n_chunks && !((a.dbg & 1) && chunk >= 1)) stage(chunk + 1);
 
         if (active && !(a.dbg & 2)) {
+            const uint32_t buf_bytes = uint32_t(chunk & 1) * uint32_t(BUF_FLOATS * 4);
             for (uint32_t base = 0; base < k_cnt; base += BATCH) {
                 if (base > 0) {
                     // more than BATCH records in this chunk: next batch (the wave's weight block
@@ -236,19 +249,29 @@ conv_tiled_kernel(const TiledArgs a)
                     ridx = k0 + min(base + uint32_t(lane), k_cnt);
                     rec_m = a.meta[ridx];
                     rec_w = a.w4[ridx];
+                    // waiting here, in the rare path, keeps the common path free of a wait for all
+                    // vector-memory loads (which would include the next chunk's staging)
+                    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
                     if (lane == 0) rec_m |= kMetaFirstOfChannel;   // input registers do not survive between batches
-                    if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
+                    if (lane < BATCH) {
+                        volatile float *wv = wlds + lane * 4;
+                        wv[0] = rec_w.x; wv[1] = rec_w.y; wv[2] = rec_w.z; wv[3] = rec_w.w;
+                    }
                 }
                 const uint32_t nb = __builtin_amdgcn_readfirstlane(min(uint32_t(BATCH), k_cnt - base));
                 asm volatile(
 #include "pconv_tiled_compute.inc"
                     : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
-                    : [recm] "v"(rec_m), [va] "v"(va), [vb] "v"(vb), [wa] "s"(wa), [cnt] "s"(nb)
+                    : [recm] "v"(rec_m), [va] "v"(va + buf_bytes), [vb] "v"(vb + buf_bytes), [wa] "s"(wa), [cnt] "s"(nb)
                     : "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
                       "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45",
                       "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57",
                       "v58", "v59", "v60", "v61", "v62", "v63",
-                      "s84", "s85", "s90", "s91", "s92", "s93", "s94", "s95", "scc", "memory");
+                      "s84", "s85", "s90", "s91", "s92", "s93", "s94", "s95", "scc");
+                // No "memory" clobber on purpose: it would make the compiler wait for the
+                // global->LDS loads of the next chunk, which are still in flight here and go to
+                // the other buffer.  What the loop reads was written before the barrier above
+                // (or by the volatile store in the batch path).
             }
         }
     }
@@ -330,7 +353,7 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
             attr_done = (e == hipSuccess);                                                            \
         }                                                                                             \
         if (e == hipSuccess)                                                                          \
-            hipLaunchKernelGGL((conv_tiled_kernel<T, L, V>), dim3(unsigned(wgs)), dim3(512), LDS_BYTES, st, a); \
+            hipLaunchKernelGGL((conv_tiled_kernel<T, L, V>), dim3(unsigned(wgs)), dim3(NWAVE * 64), LDS_BYTES, st, a); \
     } while (0)
     if (vec) PCONV_LAUNCH(float, PCONV_NCHW, true);
     else if (dtype == PCONV_F32) {

@@ -26,7 +26,7 @@ constexpr uint32_t kMetaCaseMask = 0xFFu;
 constexpr uint32_t kMetaFirstOfChannel = 0x800u;
 
 constexpr int kTileFB = 4;      // filters per wave ("slots")
-constexpr int kTileWaves = 8;   // waves per workgroup
+constexpr int kTileWaves = 16;  // waves per workgroup
 constexpr int kTileCH = 8;      // input channels staged per LDS chunk
 constexpr int kTileBatch = 32;  // records a wave fetches at a time (one per lane)
 
