@@ -36,7 +36,8 @@ constexpr int ROW_FLOATS = 64 * 6;            // one input row of all 64 patches
 constexpr int CHAN_FLOATS = 6 * ROW_FLOATS;   // 2304
 constexpr int BUF_FLOATS = CH * CHAN_FLOATS;  // 18432 floats = 72 KiB
 constexpr int WLDS_FLOATS = NWAVE * BATCH * 4;                       // weight blocks of the 16 waves
-constexpr size_t LDS_BYTES = size_t(2 * BUF_FLOATS + WLDS_FLOATS) * 4;   // 155648 of the CU's 160 KiB
+constexpr int INV_FLOATS = 2 * 64;                                  // per-lane invariants {offset, mask}
+constexpr size_t LDS_BYTES = size_t(2 * BUF_FLOATS + WLDS_FLOATS + INV_FLOATS) * 4;   // 156160 of the CU's 160 KiB
 
 static_assert(kNumCodes == 24 && FB == 4 && CH == 8 && BATCH == 32,
               "gen_tiled_compute.py is written for 24 codes, 4 slots, 8-channel chunks, 32-record batches");
@@ -60,6 +61,8 @@ struct TiledArgs {
     int py, px;                 // patches per image column / row
     int n_patches, n_tiles, n_groups, n_blocks;
     int relu, dbg;
+    int ks_log2;                // log2 of the channel split inside a workgroup (0, 1 or 2)
+    unsigned long long *ts;     // debug timestamps or null
 };
 
 template <typename T, int LAYOUT>
@@ -85,7 +88,14 @@ conv_tiled_kernel(const TiledArgs a)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int fblk = group * NWAVE + wave;
+    // The 16 waves are FW filter blocks x KS channel splits (KS = 1 for large layers).  With
+    // KS > 1 the waves of one filter block share its filters, each takes CH / KS of the 8 channels
+    // of every chunk, and the partial sums are added through LDS at the end in a fixed order:
+    // layers with few patches then still fill the machine.
+    const int ks_log2 = a.ks_log2;
+    const int fw = NWAVE >> ks_log2;                     // filter blocks per workgroup
+    const int ksplit = wave / fw;                        // this wave's channel split
+    const int fblk = group * fw + (wave - ksplit * fw);
     const bool active = fblk < a.n_blocks;
 
     const T *__restrict__ x = static_cast<const T *>(a.x);
@@ -107,8 +117,10 @@ conv_tiled_kernel(const TiledArgs a)
     // per-lane LDS byte addresses: the lane's patch in the staged buffer (the four centre columns of a
     // row / its two halo columns), and this wave's weight block
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
-    const uint32_t va = lds_base + uint32_t(lane) * 16u;
-    const uint32_t vb = lds_base + 1024u + uint32_t(lane) * 4u;
+    // (Per-lane values are deliberately recomputed where they are used, from a lane id the
+    // compiler cannot see through: only a few vector registers may stay live across the record
+    // loop, and a spill reload there would wait for the loads in flight for the next chunk.)
+    auto fresh_lane = [&]() { int l = threadIdx.x & 63; asm volatile("" : "+v"(l)); return l; };
     float *wlds = lds + 2 * BUF_FLOATS + wave * (BATCH * 4);
     const uint32_t wa = lds_base + uint32_t(2 * BUF_FLOATS + wave * (BATCH * 4)) * 4u;
 
@@ -117,25 +129,29 @@ conv_tiled_kernel(const TiledArgs a)
     // is replaced by zero when the segment is written to LDS, so all loads of a chunk are in
     // flight together.  What is valid for this lane does not change from chunk to chunk and is
     // kept as one bit mask: bits 0-5 input rows y0-1 .. y0+4, bits 8-13 input columns x0-1 .. x0+4.
-    uint32_t vmask = 0;
+    uint32_t vmask0 = 0;
 #pragma unroll
     for (int r = 0; r < 6; ++r) {
         const int iy = y0 - 1 + r, ix = x0 - 1 + r;
-        if (pvalid && iy >= 0 && iy < a.h) vmask |= 1u << r;
-        if (ix >= 0 && ix < a.w) vmask |= 0x100u << r;
+        if (pvalid && iy >= 0 && iy < a.h) vmask0 |= 1u << r;
+        if (ix >= 0 && ix < a.w) vmask0 |= 0x100u << r;
     }
     const int hw = a.h * a.w;
     // element offset of (channel 0 of the chunk, row y0-1, column x0) follows from c0; tensors have
     // fewer than 2^31 elements, so 32-bit offsets suffice (they are only used where valid)
-    const int lane_off = LAYOUT == PCONV_NCHW ? (n * a.c_in * a.h + (y0 - 1)) * a.w + x0
+    const int lane_off0 = LAYOUT == PCONV_NCHW ? (n * a.c_in * a.h + (y0 - 1)) * a.w + x0
                                               : ((n * a.h + (y0 - 1)) * a.w + x0) * a.c_in;
+    // all waves work on the same 64 patches: the per-lane invariants live in LDS, one copy
+    int *inv = reinterpret_cast<int *>(lds + 2 * BUF_FLOATS + WLDS_FLOATS);
+    if (wave == 0) { inv[2 * lane] = lane_off0; inv[2 * lane + 1] = int(vmask0); }
     // VEC path: global -> LDS directly, no registers and no vector ALU work.  Lanes whose row (or
     // halo column) lies outside the image are masked off; their LDS words were zeroed once at
     // kernel start and are never written, so they stay zero for every chunk.
     constexpr int SEGS = 48 / NWAVE;                     // (channel, row) segments per wave and chunk
     auto stage_direct = [&](int c0, float *buf) {
-        int lane_off_now = lane_off;
-        asm volatile("" : "+v"(lane_off_now));           // keeps the per-lane part of the address one register
+        const int ln = fresh_lane();
+        const int lane_off_now = inv[2 * ln];
+        const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
         const float *xf = reinterpret_cast<const float *>(x);
 #pragma unroll
         for (int kk = 0; kk < SEGS; ++kk) {
@@ -159,8 +175,9 @@ conv_tiled_kernel(const TiledArgs a)
     };
     // generic path (any layout / dtype / width): through registers, with conversion to fp32
     auto stage_load = [&](int c0, float (&t)[SEGS][6]) {
-        int lane_off_now = lane_off;
-        asm volatile("" : "+v"(lane_off_now));
+        const int ln = fresh_lane();
+        const int lane_off_now = inv[2 * ln];
+        const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
 #pragma unroll
         for (int kk = 0; kk < SEGS; ++kk) {
             const int seg = wave + NWAVE * kk;
@@ -177,6 +194,8 @@ conv_tiled_kernel(const TiledArgs a)
         }
     };
     auto stage_store = [&](int c0, float *buf, const float (&t)[SEGS][6]) {
+        const int ln = fresh_lane();
+        const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
 #pragma unroll
         for (int kk = 0; kk < SEGS; ++kk) {
             const int seg = wave + NWAVE * kk;
@@ -186,9 +205,9 @@ conv_tiled_kernel(const TiledArgs a)
 #pragma unroll
             for (int cc = 0; cc < 6; ++cc) v[cc] = (rv && ((vmask >> (8 + cc)) & 1u)) ? t[kk][cc] : 0.0f;
             float *dst = buf + (ch * 6 + r) * ROW_FLOATS;
-            *reinterpret_cast<float4 *>(dst + lane * 4) = make_float4(v[1], v[2], v[3], v[4]);
-            dst[256 + lane] = v[0];
-            dst[320 + lane] = v[5];
+            *reinterpret_cast<float4 *>(dst + ln * 4) = make_float4(v[1], v[2], v[3], v[4]);
+            dst[256 + ln] = v[0];
+            dst[320 + ln] = v[5];
         }
     };
 
@@ -197,16 +216,19 @@ conv_tiled_kernel(const TiledArgs a)
 #pragma unroll
         for (int j = 0; j < 2 * BUF_FLOATS / (NWAVE * 64 * 4); ++j)
             *reinterpret_cast<float4 *>(lds + (j * NWAVE * 64 + threadIdx.x) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
-        __syncthreads();
     }
+    __syncthreads();                                     // zeroed buffers and the per-lane invariants are visible
 
-    // The records of a (filter block, chunk) are contiguous.  The chunk boundaries (chan_ptr at
-    // multiples of CH) of up to 64 consecutive chunks sit one per lane in chunk_ptrs and are read
-    // with v_readlane.
+    // The records of a (filter block, chunk) are contiguous and ordered by channel, so this wave's
+    // share of a chunk is the range between two entries of chan_ptr.  The range bounds of up to
+    // 64 consecutive chunks sit one per lane in ptr_lo / ptr_hi and are read with v_readlane.
     const int n_chunks = (a.c_in + CH - 1) / CH;
     const uint32_t *__restrict__ ptr_row = a.chan_ptr + size_t(active ? fblk : 0) * a.row_len;
+    const int chs = CH >> ks_log2;                       // channels of a chunk per split
+    const int sub_lo = ksplit * chs, sub_hi = sub_lo + chs;
     int win_base = 0;
-    uint32_t chunk_ptrs = ptr_row[min(lane, n_chunks) * CH];
+    uint32_t ptr_lo = ptr_row[min(lane * CH + sub_lo, n_chunks * CH)];
+    uint32_t ptr_hi = ptr_row[min(lane * CH + sub_hi, n_chunks * CH)];
 
     auto stage = [&](int chunk) {
         float *buf = lds + (chunk & 1) * BUF_FLOATS;
@@ -218,37 +240,56 @@ conv_tiled_kernel(const TiledArgs a)
             stage_store(chunk * CH, buf, t);
         }
     };
-    stage(0);
-
-    for (int chunk = 0; chunk < n_chunks; ++chunk) {
-        if (chunk + 1 - win_base > 63) {                 // every 63 chunks: next window of boundaries
+    // record range of this wave for a chunk, and the fetch of its first batch: lane j gets record
+    // j (k0 + k_cnt is the next record or the padding record, always readable)
+    auto fetch_records = [&](int chunk, uint32_t &k0, uint32_t &k_cnt, uint32_t &rec_m, float4 &rec_w) {
+        if (chunk - win_base > 63) {                     // every 64 chunks: next window of bounds
             win_base = chunk;
-            chunk_ptrs = ptr_row[min(win_base + lane, n_chunks) * CH];
+            ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, n_chunks * CH)];
+            ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, n_chunks * CH)];
+            __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0) here, so that the common path needs no wait
         }
-        const uint32_t k0 = __builtin_amdgcn_readlane(chunk_ptrs, chunk - win_base);
-        const uint32_t k_cnt = active ? __builtin_amdgcn_readlane(chunk_ptrs, chunk + 1 - win_base) - k0 : 0u;
-        // first batch of this wave's records: lane j holds record j (k0 + k_cnt is the next
-        // record or the padding record, always readable)
-        uint32_t ridx = k0 + min(uint32_t(lane), k_cnt);
-        uint32_t rec_m = a.meta[ridx];
-        float4 rec_w = a.w4[ridx];
+        k0 = __builtin_amdgcn_readlane(ptr_lo, chunk - win_base);
+        k_cnt = active ? __builtin_amdgcn_readlane(ptr_hi, chunk - win_base) - k0 : 0u;
+        const uint32_t ridx = k0 + min(uint32_t(lane), k_cnt);
+        rec_m = a.meta[ridx];
+        rec_w = a.w4[ridx];
+    };
+
+    uint32_t k0, k_cnt, rec_m;
+    {
+        float4 rec_w;
+        stage(0);
+        fetch_records(0, k0, k_cnt, rec_m, rec_w);
         if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
         __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wave's staging loads have landed
-        // This chunk's inputs were requested one chunk ago; the barrier makes them (all loads are
-        // waited for before it) and the weights visible, and tells that every wave has finished
-        // the previous chunk, whose buffer is refilled right away for the next chunk.
         __syncthreads();
-        if (chunk + 1 < n_chunks && !((a.dbg & 1) && chunk >= 1)) stage(chunk + 1);
+    }
 
+    for (int chunk = 0; chunk < n_chunks; ++chunk) {
+        // Requests for the next chunk go out first and complete while this chunk is computed:
+        // its inputs (into the other LDS buffer, which every wave has finished reading: they all
+        // passed the barrier at the end of the previous iteration) and this wave's records.
+        const bool more = chunk + 1 < n_chunks;
+        const bool do_ts = a.ts && blockIdx.x == 0 && (threadIdx.x & 63) == 0;
+        if (do_ts) a.ts[(chunk * 16 + wave) * 4 + 0] = __builtin_readcyclecounter();
+        uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
+        float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (more) {
+            if (!((a.dbg & 1) && chunk >= 1)) stage(chunk + 1);
+            fetch_records(chunk + 1, nk0, nk_cnt, nrec_m, nrec_w);
+        }
+
+        if (do_ts) a.ts[(chunk * 16 + wave) * 4 + 1] = __builtin_readcyclecounter();
         if (active && !(a.dbg & 2)) {
             const uint32_t buf_bytes = uint32_t(chunk & 1) * uint32_t(BUF_FLOATS * 4);
             for (uint32_t base = 0; base < k_cnt; base += BATCH) {
                 if (base > 0) {
                     // more than BATCH records in this chunk: next batch (the wave's weight block
                     // is private, and LDS accesses of one wave execute in order)
-                    ridx = k0 + min(base + uint32_t(lane), k_cnt);
+                    const uint32_t ridx = k0 + min(base + uint32_t(lane), k_cnt);
                     rec_m = a.meta[ridx];
-                    rec_w = a.w4[ridx];
+                    const float4 rec_w = a.w4[ridx];
                     // waiting here, in the rare path, keeps the common path free of a wait for all
                     // vector-memory loads (which would include the next chunk's staging)
                     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
@@ -262,7 +303,8 @@ conv_tiled_kernel(const TiledArgs a)
                 asm volatile(
 #include "pconv_tiled_compute.inc"
                     : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
-                    : [recm] "v"(rec_m), [va] "v"(va + buf_bytes), [vb] "v"(vb + buf_bytes), [wa] "s"(wa), [cnt] "s"(nb)
+                    : [recm] "v"(rec_m), [va] "v"(lds_base + buf_bytes + uint32_t(fresh_lane()) * 16u),
+                      [vb] "v"(lds_base + buf_bytes + 1024u + uint32_t(fresh_lane()) * 4u), [wa] "s"(wa), [cnt] "s"(nb)
                     : "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
                       "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45",
                       "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57",
@@ -274,10 +316,54 @@ conv_tiled_kernel(const TiledArgs a)
                 // (or by the volatile store in the batch path).
             }
         }
+
+        if (do_ts) a.ts[(chunk * 16 + wave) * 4 + 2] = __builtin_readcyclecounter() | ((unsigned long long)k_cnt << 48);
+        // hand over to the next chunk: this wave's weights go to its LDS block (the wave has
+        // finished reading the old ones), its staging loads are waited for, and the barrier
+        // publishes all of it and tells that every wave is done with this chunk's buffer
+        if (more) {
+            if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
+            k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
+            __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+            if (do_ts) a.ts[(chunk * 16 + wave) * 4 + 3] = __builtin_readcyclecounter();
+            __syncthreads();
+        }
+    }
+
+    // ---- channel splits: add the partial sums through LDS, split 2s+1 into 2s, then 2 into 0 ----
+    if (ks_log2 > 0) {
+        __syncthreads();                                 // the staging buffers are free now
+        float4 *red = reinterpret_cast<float4 *>(lds);
+        for (int step = (1 << ks_log2) >> 1; step >= 1; step >>= 1) {
+            const bool sender = ksplit >= step && ksplit < 2 * step;
+            const bool receiver = ksplit < step;
+            // slot of (filter block fbw, split): 16 float4 per lane
+            const int fbw = wave - ksplit * fw;
+            const int slot = ((sender ? ksplit - step : ksplit) * fw + fbw) * (16 * 64);
+            if (sender) {
+#pragma unroll
+                for (int s = 0; s < FB; ++s)
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd)
+                        red[slot + (s * 4 + qd) * 64 + lane] =
+                            make_float4(acc[s][4 * qd], acc[s][4 * qd + 1], acc[s][4 * qd + 2], acc[s][4 * qd + 3]);
+            }
+            __syncthreads();
+            if (receiver) {
+#pragma unroll
+                for (int s = 0; s < FB; ++s)
+#pragma unroll
+                    for (int qd = 0; qd < 4; ++qd) {
+                        const float4 p = red[slot + (s * 4 + qd) * 64 + lane];
+                        acc[s][4 * qd] += p.x; acc[s][4 * qd + 1] += p.y; acc[s][4 * qd + 2] += p.z; acc[s][4 * qd + 3] += p.w;
+                    }
+            }
+            __syncthreads();
+        }
     }
 
     // ---- epilogue: bias, ReLU, store (filters go back to their original index) ----
-    if (!active) return;
+    if (!active || ksplit != 0) return;
     // the patch coordinates are recomputed here instead of being kept in registers across the loop
     int pidx_e = tile * 64 + lane;
     asm volatile("" : "+v"(pidx_e));
@@ -335,9 +421,17 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     a.n_patches = n * a.py * a.px;
     a.n_tiles = (a.n_patches + 63) / 64;
     a.n_blocks = h->tiled.num_blocks;
-    a.n_groups = (a.n_blocks + NWAVE - 1) / NWAVE;
+    // channel split: as long as the workgroups would not even fill the 256 compute units once
+    a.ks_log2 = 0;
+    while (a.ks_log2 < 2 &&
+           int64_t((a.n_tiles + 7) / 8) * 8 * ((a.n_blocks + (NWAVE >> a.ks_log2) - 1) / (NWAVE >> a.ks_log2)) <= 128)
+        ++a.ks_log2;
+    { const char *e = getenv("PCONV_KS_LOG2"); if (e) a.ks_log2 = atoi(e) & 3; if (a.ks_log2 > 2) a.ks_log2 = 2; }
+    const int fw = NWAVE >> a.ks_log2;
+    a.n_groups = (a.n_blocks + fw - 1) / fw;
     a.relu = relu;
     { const char *e = getenv("PCONV_DEBUG_FLAGS"); a.dbg = e ? atoi(e) : 0; }
+    { const char *e = getenv("PCONV_DEBUG_TS"); a.ts = e ? reinterpret_cast<unsigned long long *>(strtoull(e, nullptr, 0)) : nullptr; }
     const bool vec = dtype == PCONV_F32 && layout == PCONV_NCHW && (win % 4 == 0) &&
                      (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
     const int64_t wgs = int64_t((a.n_tiles + 7) / 8) * 8 * a.n_groups;
