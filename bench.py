@@ -16,6 +16,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_VEC_TFLOPS = 157.3      # MI355X fp32 vector peak (256 CU x 2.4 GHz x 256 flop/clk/CU)
 PEAK_HBM_GBS = 8000.0
+# HBM bytes of the 13 conv launches of one step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled
+# by a 256 MiB device copy (x2.000 / x1.000); see profiles/pconv_conv2d_vgg16_stack_n32_fp32.md.
+# Valid for the default workload (batch 32) only.
+MEASURED_TRAFFIC_BYTES_BATCH32 = 3.624e9
 
 
 def main():
@@ -26,6 +30,9 @@ def main():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--policy", type=int, default=0, help="kernel policy (0 auto, 1 generic, 2 tiled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-copy-mb", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB (calibrates rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the batch would shard across GPUs with no "
@@ -80,6 +87,12 @@ def main():
                                    P.NCHW, P.F32, stream)
                 cur = ly["p"]
 
+    if args.profile_copy_mb:
+        src = torch.empty(args.profile_copy_mb * 2**20 // 4, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -116,7 +129,9 @@ def main():
         "config": {"workload": f"vgg16_3x3_stack_13conv_batch{n}_fp32_8pattern_conn3.6x",
                    "global_batch": n, "layout": "nchw", "kernel_policy": args.policy},
         "roofline": {"bound": "alu", "achieved": round(achieved, 3), "peak": PEAK_VEC_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_VEC_TFLOPS, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_VEC_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES_BATCH32 if (n == 32 and args.policy == 0) else None,
+                     "algorithmic_flop": total_flop, "algorithmic_bytes": sum(ly["bytes"] for ly in layers),
                      "kernel": "pconv_conv2d (13 launches per step, summed)",
                      "conv_ms_per_step": round(conv_ms_total, 4),
                      "stack_roof_frac": round(sum(max(ly["flop"] / (PEAK_VEC_TFLOPS * 1e12),
