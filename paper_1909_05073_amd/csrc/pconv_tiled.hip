@@ -72,8 +72,8 @@ __device__ __forceinline__ size_t act_at(int n, int c, int y, int x, int C, int 
     return ((size_t(n) * H + y) * W + x) * C + c;
 }
 
-// VEC: fp32 NCHW tensors whose width is a multiple of 4 and whose base is 16-byte aligned move
-// the four centre columns of a row (and the four outputs of a row) with one 128-bit access.
+// VEC: fp32 NCHW tensors at least 4 wide move the four centre columns of a patch row (and the four
+// outputs of a row) with one 128-bit access; the inputs go from global memory straight to LDS.
 template <typename T, int LAYOUT, bool VEC>
 __global__ void __launch_bounds__(1024, 4)   // 4 waves per SIMD: at most 128 VGPRs
 conv_tiled_kernel(const TiledArgs a)
@@ -107,7 +107,11 @@ conv_tiled_kernel(const TiledArgs a)
     const int per_img = a.py * a.px;
     const int n = pvalid ? pidx / per_img : 0;
     const int prem = pvalid ? pidx - n * per_img : 0;
-    const int y0 = (prem / a.px) * 4, x0 = (prem % a.px) * 4;
+    // VEC: the last patch of a row is shifted left so that it ends at the image edge (it then
+    // overlaps its neighbour and both compute identical values for the shared columns): the four
+    // centre columns of a patch row are then always inside the image.
+    const int y0 = (prem / a.px) * 4;
+    const int x0 = VEC ? min((prem % a.px) * 4, a.w - 4) : (prem % a.px) * 4;
 
     // accumulators: slot s, output (row i, column k) of the patch = acc[s][4 * i + k].  The record
     // loop is assembly with a fixed register map, so each vector is pinned to its registers there.
@@ -369,7 +373,8 @@ conv_tiled_kernel(const TiledArgs a)
     asm volatile("" : "+v"(pidx_e));
     if (pidx_e >= a.n_patches) return;
     const int n_e = pidx_e / per_img, prem_e = pidx_e - n_e * per_img;
-    const int ye = (prem_e / a.px) * 4, xe = (prem_e % a.px) * 4;
+    const int ye = (prem_e / a.px) * 4;
+    const int xe = VEC ? min((prem_e % a.px) * 4, a.w - 4) : (prem_e % a.px) * 4;
     const int ho = a.h, wo = a.w;
 #pragma unroll
     for (int s = 0; s < FB; ++s) {
@@ -432,8 +437,7 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     a.relu = relu;
     { const char *e = getenv("PCONV_DEBUG_FLAGS"); a.dbg = e ? atoi(e) : 0; }
     { const char *e = getenv("PCONV_DEBUG_TS"); a.ts = e ? reinterpret_cast<unsigned long long *>(strtoull(e, nullptr, 0)) : nullptr; }
-    const bool vec = dtype == PCONV_F32 && layout == PCONV_NCHW && (win % 4 == 0) &&
-                     (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
+    const bool vec = dtype == PCONV_F32 && layout == PCONV_NCHW && win >= 4;
     const int64_t wgs = int64_t((a.n_tiles + 7) / 8) * 8 * a.n_groups;
     if (wgs > 0x7FFFFFFF) { set_error("pconv_conv2d: too many workgroups"); return PCONV_UNSUPPORTED; }
     hipStream_t st = static_cast<hipStream_t>(stream);
