@@ -37,7 +37,8 @@ constexpr int CHAN_FLOATS = 6 * ROW_FLOATS;   // 2304
 constexpr int BUF_FLOATS = CH * CHAN_FLOATS;  // 18432 floats = 72 KiB
 constexpr int WLDS_FLOATS = NWAVE * BATCH * 4;                       // weight blocks of the 16 waves
 constexpr int INV_FLOATS = 2 * 64;                                  // per-lane invariants {offset, mask}
-constexpr size_t LDS_BYTES = size_t(2 * BUF_FLOATS + WLDS_FLOATS + INV_FLOATS) * 4;   // 156160 of the CU's 160 KiB
+constexpr int TICK_FLOATS = 4;                                      // two staging ticket counters (+ pad)
+constexpr size_t LDS_BYTES = size_t(2 * BUF_FLOATS + WLDS_FLOATS + INV_FLOATS + TICK_FLOATS) * 4;   // 156176 of the CU's 160 KiB
 
 static_assert(kNumCodes == 24 && FB == 4 && CH == 8 && BATCH == 32,
               "gen_tiled_compute.py is written for 24 codes, 4 slots, 8-channel chunks, 32-record batches");
@@ -147,19 +148,24 @@ conv_tiled_kernel(const TiledArgs a)
                                               : ((n * a.h + (y0 - 1)) * a.w + x0) * a.c_in;
     // all waves work on the same 64 patches: the per-lane invariants live in LDS, one copy
     int *inv = reinterpret_cast<int *>(lds + 2 * BUF_FLOATS + WLDS_FLOATS);
+    // staging tickets (VEC path): the 16 units of a chunk (3 (channel, row) segments each) are
+    // handed out in the order in which waves finish the previous chunk's records, so the waves with
+    // few records do the staging and the busiest wave does none
+    unsigned *tick = reinterpret_cast<unsigned *>(lds + 2 * BUF_FLOATS + WLDS_FLOATS + INV_FLOATS);
+    if (threadIdx.x == 0) { tick[0] = 0; tick[1] = 0; }
     if (wave == 0) { inv[2 * lane] = lane_off0; inv[2 * lane + 1] = int(vmask0); }
     // VEC path: global -> LDS directly, no registers and no vector ALU work.  Lanes whose row (or
     // halo column) lies outside the image are masked off; their LDS words were zeroed once at
     // kernel start and are never written, so they stay zero for every chunk.
     constexpr int SEGS = 48 / NWAVE;                     // (channel, row) segments per wave and chunk
-    auto stage_direct = [&](int c0, float *buf) {
+    auto stage_direct = [&](int c0, float *buf, int unit) {
         const int ln = fresh_lane();
         const int lane_off_now = inv[2 * ln];
         const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
         const float *xf = reinterpret_cast<const float *>(x);
 #pragma unroll
         for (int kk = 0; kk < SEGS; ++kk) {
-            const int seg = wave + NWAVE * kk;           // 0..47, uniform per wave
+            const int seg = unit + NWAVE * kk;           // 0..47, uniform per wave
             const int ch = seg / 6, r = seg - ch * 6;
             const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
             const float *src = xf + (lane_off_now + (c0 + ch) * hw + r * a.w);
@@ -237,7 +243,7 @@ conv_tiled_kernel(const TiledArgs a)
     auto stage = [&](int chunk) {
         float *buf = lds + (chunk & 1) * BUF_FLOATS;
         if (VEC) {
-            stage_direct(chunk * CH, buf);
+            stage_direct(chunk * CH, buf, wave);
         } else {
             float t[SEGS][6];
             stage_load(chunk * CH, t);
@@ -276,15 +282,18 @@ conv_tiled_kernel(const TiledArgs a)
         // passed the barrier at the end of the previous iteration) and this wave's records.
         const bool more = chunk + 1 < n_chunks;
         const bool do_ts = a.ts && blockIdx.x == 0 && (threadIdx.x & 63) == 0;
-        if (do_ts) a.ts[(chunk * 16 + wave) * 4 + 0] = __builtin_readcyclecounter();
+        if (do_ts) a.ts[(chunk * 16 + wave) * 6 + 0] = __builtin_readcyclecounter();
         uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
         float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
+        const bool do_stage = more && !((a.dbg & 1) && chunk >= 1);
         if (more) {
-            if (!((a.dbg & 1) && chunk >= 1)) stage(chunk + 1);
+            if (!VEC && do_stage) stage(chunk + 1);       // register path: fixed assignment
             fetch_records(chunk + 1, nk0, nk_cnt, nrec_m, nrec_w);
         }
+        // the ticket counter of the chunk after next is idle during this iteration: reset it
+        if (VEC && threadIdx.x == 0) tick[chunk & 1] = 0;
 
-        if (do_ts) a.ts[(chunk * 16 + wave) * 4 + 1] = __builtin_readcyclecounter();
+        if (do_ts) a.ts[(chunk * 16 + wave) * 6 + 1] = __builtin_readcyclecounter();
         if (active && !(a.dbg & 2)) {
             const uint32_t buf_bytes = uint32_t(chunk & 1) * uint32_t(BUF_FLOATS * 4);
             for (uint32_t base = 0; base < k_cnt; base += BATCH) {
@@ -321,7 +330,20 @@ conv_tiled_kernel(const TiledArgs a)
             }
         }
 
-        if (do_ts) a.ts[(chunk * 16 + wave) * 4 + 2] = __builtin_readcyclecounter() | ((unsigned long long)k_cnt << 48);
+        if (do_ts) { a.ts[(chunk * 16 + wave) * 6 + 2] = __builtin_readcyclecounter(); a.ts[(chunk * 16 + wave) * 6 + 4] = k_cnt; }
+        // stage the next chunk: take units until none is left (the other buffer is free: every
+        // wave passed the barrier at the end of the previous iteration)
+        if (VEC && do_stage) {
+            float *buf = lds + ((chunk + 1) & 1) * BUF_FLOATS;
+            for (;;) {
+                unsigned t = 0;
+                if (fresh_lane() == 0)
+                    t = __hip_atomic_fetch_add(&tick[(chunk + 1) & 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                t = __builtin_amdgcn_readfirstlane(t);
+                if (t >= unsigned(NWAVE)) break;
+                stage_direct((chunk + 1) * CH, buf, int(t));
+            }
+        }
         // hand over to the next chunk: this wave's weights go to its LDS block (the wave has
         // finished reading the old ones), its staging loads are waited for, and the barrier
         // publishes all of it and tells that every wave is done with this chunk's buffer
@@ -329,7 +351,7 @@ conv_tiled_kernel(const TiledArgs a)
             if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
             k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
             __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
-            if (do_ts) a.ts[(chunk * 16 + wave) * 4 + 3] = __builtin_readcyclecounter();
+            if (do_ts) a.ts[(chunk * 16 + wave) * 6 + 3] = __builtin_readcyclecounter();
             __syncthreads();
         }
     }
