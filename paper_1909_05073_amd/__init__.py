@@ -70,6 +70,8 @@ def lib():
     L.pconv_debug_unpack.argtypes = [vp, vp]
     L.pconv_set_kernel_policy.restype = ip
     L.pconv_set_kernel_policy.argtypes = [ip]
+    L.pconv_debug_set_tiling.restype = ip
+    L.pconv_debug_set_tiling.argtypes = [ip, ip]
     L.pconv_last_error.restype = C.c_char_p
     L.pconv_last_error.argtypes = []
     _lib = L
@@ -78,7 +80,7 @@ def lib():
 
 EXPORTED_SYMBOLS = ["pconv_pack", "pconv_conv2d", "pconv_free", "pconv_maxpool2x2",
                     "pconv_get_info", "pconv_debug_export", "pconv_debug_pack_host", "pconv_debug_unpack",
-                    "pconv_set_kernel_policy", "pconv_last_error"]
+                    "pconv_set_kernel_policy", "pconv_debug_set_tiling", "pconv_last_error"]
 
 
 def _check(rc: int):
@@ -152,6 +154,10 @@ def pconv_maxpool2x2(x_ptr: int, y_ptr: int, n: int, c: int, h: int, w: int, lay
 
 def pconv_set_kernel_policy(policy: int):
     _check(lib().pconv_set_kernel_policy(int(policy)))
+
+
+def pconv_debug_set_tiling(waves: int = 0, ks_log2: int = -1):
+    _check(lib().pconv_debug_set_tiling(int(waves), int(ks_log2)))
 
 
 def pconv_debug_export(handle: Handle) -> dict:

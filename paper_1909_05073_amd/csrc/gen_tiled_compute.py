@@ -11,15 +11,16 @@ vector registers (an FMA with a scalar-register operand issues at half the rate 
 Output: a C string-literal include (one inline-asm template).  Register map (fixed; the C++ side
 pins / clobbers the same registers):
     v[64 + 16*slot + 4*row + col]   accumulators of the 4x4 output patch of a slot (4 slots)
-    v[28 + 6*r + m]                 6x6 input neighbourhood of the lane's patch, row r in 0..5; within a
-                                    row m = 0..3 are columns x0..x0+3, m = 4 is x0-1, m = 5 is x0+4
+    v[28 + 4*r + m]                 input rows r = 0..5 of the lane's patch, columns x0..x0+3 (m = 0..3)
+    v[52 + r], v[58 + r]            the halo columns x0-1 and x0+4 of row r
     v[24:27]                        the record's four weights (same value in every lane)
     v22, v23                        LDS addresses
     s84 record index, s85 record word, s90 scratch, s[92:93] address of body 0, s[94:95] target
-Operands: %[recm] per-lane record words (lane j = record j), %[va] %[vb] per-lane LDS byte
-addresses of the lane's patch in the staged buffer (the four centre columns of a row / the two
-halo columns, which sit 256 bytes apart), %[wa] LDS byte address
-of this wave's weight block (SGPR; 16 bytes per record), %[cnt] number of records (SGPR, 1..32).
+Operands: %[recm] per-lane record words (lane j = record j), %[va] per-lane LDS byte address of
+the lane's patch in the staged buffer (a staged channel is nine 1 KiB blocks of one 16-byte
+quad per lane: the six rows, then the twelve halo values), %[wa] LDS byte address
+of this wave's weight block (SGPR; 16 bytes per record), %[first] %[cnt] the records to run
+(SGPRs; first <= cnt <= 32; nothing is done when they are equal).
 """
 import os
 import sys
@@ -31,8 +32,8 @@ STRIDE_LOG2 = 9
 CODE_MASKS = [0x03A, 0x09A, 0x0B8, 0x0B2, 0x01B, 0x036, 0x0D8, 0x1B0, 0x113, 0x074, 0x191, 0x05C,
               0x007, 0x038, 0x1C0, 0x001, 0x002, 0x004, 0x008, 0x010, 0x020, 0x040, 0x080, 0x100]
 SLOTS = 4
-CHAN_BYTES = 6 * 64 * 6 * 4      # one staged channel: 6 rows x 64 patches x 6 floats
-ROW_BYTES = 64 * 6 * 4
+QUAD_BYTES = 64 * 16             # one 16-byte quad of every lane
+CHAN_BYTES = 9 * QUAD_BYTES      # one staged channel: 64 patches x 36 floats
 
 
 def fetch(lines):
@@ -54,6 +55,8 @@ def fetch(lines):
 
 
 def jump(lines):
+    if 'seq' in EXP:
+        return
     if 'nojump' in EXP:
         lines += ["s_and_b32 s90, s85, 0", "s_min_u32 s90, s90, 95", "s_lshl_b32 s90, s90, 9",
                   "s_add_u32 s94, s92, s90", "s_addc_u32 s95, s93, 0", "s_branch TABLE_%="]
@@ -70,39 +73,44 @@ def jump(lines):
 
 def in_reg(row, col):
     """Register of input (row, col) of the 6x6 neighbourhood; col 0 is x0-1, col 5 is x0+4."""
-    m = 4 if col == 0 else (5 if col == 5 else col - 1)
-    return INP + 6 * row + m
+    if col == 0:
+        return INP + 24 + row
+    if col == 5:
+        return INP + 30 + row
+    return INP + 4 * row + col - 1
 
 
 def generate():
     L = []
     L += [
-        "s_cmp_eq_u32 %[cnt], 0",
+        "s_cmp_ge_u32 %[first], %[cnt]",
         "s_cbranch_scc1 DONE_%=",
         "s_getpc_b64 s[92:93]",
         "BASE_%=:",
         "s_add_u32 s92, s92, TABLE_%=-BASE_%=",
         "s_addc_u32 s93, s93, 0",
-        "s_mov_b32 s84, 0",
+        "s_mov_b32 s84, %[first]",
     ]
     fetch(L)
+    if 'seq' in EXP:
+        L.append("s_branch TABLE_%=")
     # out of line: a new channel starts, reload the lane's 6x6 neighbourhood from LDS
     L += [
         "PATCH_%=:",
-        "s_bfe_u32 s90, s85, 0x30008",
+        "s_bfe_u32 s90, s85, %[chbfe]",
         "s_mul_i32 s90, s90, %d" % CHAN_BYTES,
         "v_add_u32 v22, s90, %[va]",
-        "v_add_u32 v23, s90, %[vb]",
     ]
-    for r in range(6):
-        b = INP + 6 * r
-        L.append("ds_read_b128 v[%d:%d], v22 offset:%d" % (b, b + 3, r * ROW_BYTES))
-        L.append("ds_read2st64_b32 v[%d:%d], v23 offset0:%d offset1:%d" % (b + 4, b + 5, 6 * r, 6 * r + 1))
+    for k in range(9):
+        b = INP + 4 * k
+        L.append("ds_read_b128 v[%d:%d], v22 offset:%d" % (b, b + 3, k * QUAD_BYTES))
     jump(L)
     L.append(".p2align %d" % STRIDE_LOG2)
     L.append("TABLE_%=:")
     for slot in range(SLOTS):
         for mask in CODE_MASKS:
+            if 'same' in EXP:
+                mask = 0x03A
             L.append("s_waitcnt lgkmcnt(0)")
             j = 0
             for t in range(9):
@@ -120,7 +128,10 @@ def generate():
                 "s_cbranch_scc1 DONE_%=",
             ]
             fetch(L)
-            L.append(".p2align %d" % STRIDE_LOG2)
+            if 'seq' not in EXP:
+                L.append(".p2align %d" % STRIDE_LOG2)
+    if 'seq' in EXP:
+        L.append("s_branch TABLE_%=")
     L.append("DONE_%=:")
     return L
 

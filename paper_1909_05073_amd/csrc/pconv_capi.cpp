@@ -62,6 +62,12 @@ int pconv_set_kernel_policy(int policy)
     return PCONV_OK;
 }
 
+int pconv_debug_set_tiling(int waves, int ks_log2)
+{
+    set_tiled_tuning(waves, ks_log2);
+    return PCONV_OK;
+}
+
 static int pack_impl(const float *w_dense, const uint8_t *pattern_id, const uint8_t *conn,
                      const uint16_t *table, int num_patterns, int c_out, int c_in,
                      pconv_dtype weight_dtype, pconv_handle **out, bool to_device)

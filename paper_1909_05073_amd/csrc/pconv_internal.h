@@ -74,6 +74,9 @@ int launch_conv_generic(const pconv_handle *h, const void *x, void *y, const flo
 int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
                       int hin, int win, int stride, int layout, int dtype, int relu, void *stream);
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype);
+// Test override of the tiled kernel's launch choices: waves per workgroup (8 or 16, anything else =
+// automatic) and log2 of the channel split inside a workgroup (0..2, anything else = automatic).
+void set_tiled_tuning(int waves, int ks_log2);
 int launch_maxpool2x2(const void *x, void *y, int n, int c, int h, int w, int layout, int dtype,
                       void *stream);
 

@@ -1,19 +1,21 @@
 // Register-tiled PCONV kernel for gfx950 (stride 1).
 //
-// Work decomposition.  A workgroup of 16 waves owns 64 "patches" (a patch = a 4x4 block of output
-// pixels of one image; one patch per lane) and 64 filters (4 per wave, its "slots").  One
-// workgroup fills a compute unit with 4 waves per SIMD: a single wave issues a vector
-// instruction only about every 6.5 cycles, so it takes three to four of them to keep a SIMD busy.
+// Work decomposition.  A workgroup of NW waves owns 64 "patches" (a patch = a 4x4 block of output
+// pixels of one image; one patch per lane) and 4 * NW filters (4 per wave, its "slots").  Two shapes
+// are built: 16 waves with 8-channel chunks (one workgroup fills a compute unit), and 8 waves with
+// 4-channel chunks (two workgroups share a compute unit, which evens out layers whose workgroup
+// count is a poor multiple of the 256 compute units).  Either way a SIMD runs 4 waves: a single
+// wave issues a vector instruction only about every 6.5 cycles, so it takes three to four of them
+// to keep a SIMD busy.
 //
-// The input channels are walked in chunks of 8 through two LDS buffers.  For a chunk, all 1024
-// threads stage the 6x6 input neighbourhood of every patch into LDS (zero outside the image, so
-// the inner loops have no bounds tests) while the previous chunk is being computed, and every wave
-// copies the weights of its records for the chunk into its own LDS block.  Then each wave walks
-// its records: a record is one (kernel, code) pair, i.e. up to four
-// kept taps of one 3x3 kernel of one of the wave's filters.  When a record starts a new input
-// channel the lane reloads its 6x6 neighbourhood from LDS (six b128 + six b64 reads) and keeps it
-// in registers for all of the wave's filters connected to that channel; the record itself costs
-// 16 FMAs per kept tap on the slot's 16 accumulator registers.
+// The input channels are walked in chunks of CH through two LDS buffers.  For a chunk, the 6x6 input
+// neighbourhood of every patch is staged into LDS (zero outside the image, so the inner loops have
+// no bounds tests) while the previous chunk is being computed, and every wave copies the weights
+// of its records for the chunk into its own LDS block.  Then each wave walks its records: a
+// record is one (kernel, code) pair, i.e. up to four kept taps of one 3x3 kernel of one of the
+// wave's filters.  When a record starts a new input channel the lane reloads its 6x6 neighbourhood
+// from LDS (nine 128-bit reads) and keeps it in registers for all of the wave's filters connected
+// to that channel; the record itself costs 16 FMAs per kept tap on the slot's 16 accumulators.
 //
 // The record loop is generated assembly (gen_tiled_compute.py): the pattern of a kernel selects
 // straight-line code with compile-time register indices (paper: per-pattern generated code, one
@@ -30,18 +32,33 @@ namespace {
 
 struct bf16_t { uint16_t bits; };
 
-constexpr int FB = kTileFB, NWAVE = kTileWaves, CH = kTileCH, BATCH = kTileBatch;
-constexpr int ROW_FLOATS = 64 * 6;            // one input row of all 64 patches: columns x0..x0+3 as [64][4],
-                                              // then column x0-1 as [64], then column x0+4 as [64]
-constexpr int CHAN_FLOATS = 6 * ROW_FLOATS;   // 2304
-constexpr int BUF_FLOATS = CH * CHAN_FLOATS;  // 18432 floats = 72 KiB
-constexpr int WLDS_FLOATS = NWAVE * BATCH * 4;                       // weight blocks of the 16 waves
-constexpr int INV_FLOATS = 2 * 64;                                  // per-lane invariants {offset, mask}
-constexpr int TICK_FLOATS = 4;                                      // two staging ticket counters (+ pad)
-constexpr size_t LDS_BYTES = size_t(2 * BUF_FLOATS + WLDS_FLOATS + INV_FLOATS + TICK_FLOATS) * 4;   // 156176 of the CU's 160 KiB
+constexpr int FB = kTileFB, BATCH = kTileBatch;
+// A staged channel is nine blocks of one 16-byte quad per patch: blocks 0-5 hold columns x0..x0+3
+// of input rows y0-1..y0+4; blocks 6-8 hold the patch's twelve halo values e = 0..11 (quad e / 4,
+// element e % 4): e < 6 is column x0-1 of row e, e >= 6 is column x0+4 of row e - 6.  A lane reads its
+// whole 6x6 neighbourhood with nine 128-bit LDS reads.
+constexpr int QUAD_FLOATS = 64 * 4;
+constexpr int CHAN_FLOATS = 9 * QUAD_FLOATS;  // 2304
+constexpr int INV_FLOATS = 2 * 64;            // per-lane invariants {offset, mask}
+constexpr int SYNC_WORDS = 8;                 // counters that order the waves
+constexpr int HALO_TAB_WORDS = 12 * 64;       // source offsets of the halo loads (VEC)
 
-static_assert(kNumCodes == 24 && FB == 4 && CH == 8 && BATCH == 32,
-              "gen_tiled_compute.py is written for 24 codes, 4 slots, 8-channel chunks, 32-record batches");
+template <int NW, int CH> struct Shape {
+    static constexpr int BUF_FLOATS = CH * CHAN_FLOATS;        // one chunk
+    static constexpr int WLDS_FLOATS = NW * BATCH * 4;         // weight blocks of the waves
+    static constexpr int OFF_W = 2 * BUF_FLOATS;
+    static constexpr int OFF_INV = OFF_W + WLDS_FLOATS;
+    static constexpr int OFF_SYNC = OFF_INV + INV_FLOATS;
+    static constexpr int OFF_HALO = OFF_SYNC + SYNC_WORDS;
+    // 16 waves x 8 channels: 159264 of the compute unit's 163840 bytes; 8 x 4: 81440 (two fit)
+    static constexpr size_t LDS_BYTES = size_t(OFF_HALO + HALO_TAB_WORDS) * 4;
+    static constexpr int UNITS = 2 * CH;                       // staging units of half a channel per chunk
+    static constexpr int SEGS = CH * 6 / NW;                   // (channel, row) segments per wave (register path)
+    static_assert(CH * 6 % NW == 0 && UNITS % 4 == 0 && CH <= kTileCH && kTileCH % CH == 0, "unsupported shape");
+};
+
+static_assert(kNumCodes == 24 && FB == 4 && BATCH == 32 && kTileCH == 8,
+              "gen_tiled_compute.py is written for 24 codes, 4 slots, 32-record batches, channel field of 3 bits");
 
 __device__ __forceinline__ float ld_act(const float *p, size_t i) { return p[i]; }
 __device__ __forceinline__ float ld_act(const bf16_t *p, size_t i) { return __uint_as_float(uint32_t(p[i].bits) << 16); }
@@ -61,9 +78,8 @@ struct TiledArgs {
     int n_img, c_in, row_len, h, w, c_out;
     int py, px;                 // patches per image column / row
     int n_patches, n_tiles, n_groups, n_blocks;
-    int relu, dbg;
+    int relu;
     int ks_log2;                // log2 of the channel split inside a workgroup (0, 1 or 2)
-    unsigned long long *ts;     // debug timestamps or null
 };
 
 template <typename T, int LAYOUT>
@@ -75,10 +91,12 @@ __device__ __forceinline__ size_t act_at(int n, int c, int y, int x, int C, int 
 
 // VEC: fp32 NCHW tensors at least 4 wide move the four centre columns of a patch row (and the four
 // outputs of a row) with one 128-bit access; the inputs go from global memory straight to LDS.
-template <typename T, int LAYOUT, bool VEC>
-__global__ void __launch_bounds__(1024, 4)   // 4 waves per SIMD: at most 128 VGPRs
+template <typename T, int LAYOUT, bool VEC, int NW, int CH>
+__global__ void __launch_bounds__(NW * 64, 4)   // 4 waves per SIMD: at most 128 VGPRs
 conv_tiled_kernel(const TiledArgs a)
 {
+    using S = Shape<NW, CH>;
+    constexpr int BUF_FLOATS = S::BUF_FLOATS;
     extern __shared__ __attribute__((aligned(16))) float lds[];
 
     // workgroup id -> (tile, filter group); the groups of one tile share an XCD (ids equal mod 8)
@@ -89,12 +107,12 @@ conv_tiled_kernel(const TiledArgs a)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // The 16 waves are FW filter blocks x KS channel splits (KS = 1 for large layers).  With
-    // KS > 1 the waves of one filter block share its filters, each takes CH / KS of the 8 channels
-    // of every chunk, and the partial sums are added through LDS at the end in a fixed order:
-    // layers with few patches then still fill the machine.
+    // The waves are FW filter blocks x KS channel splits (KS = 1 for large layers).  With KS > 1
+    // the waves of one filter block share its filters, each takes CH / KS of the channels of every
+    // chunk, and the partial sums are added through LDS at the end in a fixed order: layers with
+    // few patches then still fill the machine.
     const int ks_log2 = a.ks_log2;
-    const int fw = NWAVE >> ks_log2;                     // filter blocks per workgroup
+    const int fw = NW >> ks_log2;                        // filter blocks per workgroup
     const int ksplit = wave / fw;                        // this wave's channel split
     const int fblk = group * fw + (wave - ksplit * fw);
     const bool active = fblk < a.n_blocks;
@@ -119,21 +137,19 @@ conv_tiled_kernel(const TiledArgs a)
     v16f acc[FB];
 #pragma unroll
     for (int s = 0; s < FB; ++s) acc[s] = 0.0f;
-    // per-lane LDS byte addresses: the lane's patch in the staged buffer (the four centre columns of a
-    // row / its two halo columns), and this wave's weight block
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
     // (Per-lane values are deliberately recomputed where they are used, from a lane id the
     // compiler cannot see through: only a few vector registers may stay live across the record
     // loop, and a spill reload there would wait for the loads in flight for the next chunk.)
     auto fresh_lane = [&]() { int l = threadIdx.x & 63; asm volatile("" : "+v"(l)); return l; };
-    float *wlds = lds + 2 * BUF_FLOATS + wave * (BATCH * 4);
-    const uint32_t wa = lds_base + uint32_t(2 * BUF_FLOATS + wave * (BATCH * 4)) * 4u;
+    float *wlds = lds + S::OFF_W + wave * (BATCH * 4);   // this wave's weight block
+    const uint32_t wa = lds_base + uint32_t(S::OFF_W + wave * (BATCH * 4)) * 4u;
 
-    // ---- staging helpers: every thread owns 6 (channel, row) segments of its lane's patch ----
-    // Loads are branch-free: an out-of-image element reads element 0 of the tensor instead and
-    // is replaced by zero when the segment is written to LDS, so all loads of a chunk are in
-    // flight together.  What is valid for this lane does not change from chunk to chunk and is
-    // kept as one bit mask: bits 0-5 input rows y0-1 .. y0+4, bits 8-13 input columns x0-1 .. x0+4.
+    // ---- staging ----
+    // Loads are branch-free: an out-of-image element is not loaded (VEC) or reads element 0 of the
+    // tensor and is replaced by zero when the segment is written to LDS.  What is valid for this
+    // lane does not change from chunk to chunk and is kept as one bit mask: bits 0-5 input rows
+    // y0-1 .. y0+4, bits 8-13 input columns x0-1 .. x0+4.
     uint32_t vmask0 = 0;
 #pragma unroll
     for (int r = 0; r < 6; ++r) {
@@ -147,50 +163,73 @@ conv_tiled_kernel(const TiledArgs a)
     const int lane_off0 = LAYOUT == PCONV_NCHW ? (n * a.c_in * a.h + (y0 - 1)) * a.w + x0
                                               : ((n * a.h + (y0 - 1)) * a.w + x0) * a.c_in;
     // all waves work on the same 64 patches: the per-lane invariants live in LDS, one copy
-    int *inv = reinterpret_cast<int *>(lds + 2 * BUF_FLOATS + WLDS_FLOATS);
-    // staging tickets (VEC path): the 16 units of a chunk (3 (channel, row) segments each) are
-    // handed out in the order in which waves finish the previous chunk's records, so the waves with
-    // few records do the staging and the busiest wave does none
-    unsigned *tick = reinterpret_cast<unsigned *>(lds + 2 * BUF_FLOATS + WLDS_FLOATS + INV_FLOATS);
-    if (threadIdx.x == 0) { tick[0] = 0; tick[1] = 0; }
+    int *inv = reinterpret_cast<int *>(lds + S::OFF_INV);
+    unsigned *sync_words = reinterpret_cast<unsigned *>(lds + S::OFF_SYNC);
+    if (threadIdx.x < SYNC_WORDS) sync_words[threadIdx.x] = 0;
     if (wave == 0) { inv[2 * lane] = lane_off0; inv[2 * lane + 1] = int(vmask0); }
+    // VEC path: the twelve halo values of a patch are fetched by twelve one-word loads per channel,
+    // each of which fills 64 consecutive words of the halo blocks: word i of load j belongs to patch
+    // 16 * (j % 4) + i / 4 and is its halo value e = 4 * (j / 4) + i % 4.  The element offset of that
+    // value in channel 0 (or -1 outside the image) is the same for every chunk: tabulated once.
+    int *halo_tab = reinterpret_cast<int *>(lds + S::OFF_HALO);
+    if (VEC) {
+        for (int t = threadIdx.x; t < HALO_TAB_WORDS; t += NW * 64) {
+            const int j = t >> 6, i = t & 63;
+            const int e = 4 * (j >> 2) + (i & 3);
+            const int pidx_h = tile * 64 + 16 * (j & 3) + (i >> 2);
+            const int n_h = pidx_h / per_img, prem_h = pidx_h - n_h * per_img;
+            const int iy = (prem_h / a.px) * 4 - 1 + (e < 6 ? e : e - 6);
+            const int xh = min((prem_h % a.px) * 4, a.w - 4);
+            const int ix = e < 6 ? xh - 1 : xh + 4;
+            const bool ok = pidx_h < a.n_patches && iy >= 0 && iy < a.h && ix >= 0 && ix < a.w;
+            halo_tab[t] = ok ? (n_h * a.c_in * a.h + iy) * a.w + ix : -1;
+        }
+    }
     // VEC path: global -> LDS directly, no registers and no vector ALU work.  Lanes whose row (or
-    // halo column) lies outside the image are masked off; their LDS words were zeroed once at
+    // halo value) lies outside the image are masked off; their LDS words were zeroed once at
     // kernel start and are never written, so they stay zero for every chunk.
-    constexpr int SEGS = 48 / NWAVE;                     // (channel, row) segments per wave and chunk
+    // One unit of staging work = half a channel: three rows and six halo loads.
     auto stage_direct = [&](int c0, float *buf, int unit) {
         const int ln = fresh_lane();
-        const int lane_off_now = inv[2 * ln];
-        const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
-        const float *xf = reinterpret_cast<const float *>(x);
+        const int ch = unit >> 1, half = unit & 1;
+        const bool cv = c0 + ch < a.c_in;
+        const float *xc = reinterpret_cast<const float *>(x) + (c0 + ch) * hw;
+        float *cbuf = buf + ch * CHAN_FLOATS;
+        // The LDS address of lane 0's element goes to M0 and every lane adds lane * size.  Written
+        // as assembly so that the compiler does not track these loads: it would otherwise wait for
+        // them before the record loop (they are waited for explicitly before they are published).
+        {
+            const int lane_off_now = inv[2 * ln];
+            const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
 #pragma unroll
-        for (int kk = 0; kk < SEGS; ++kk) {
-            const int seg = unit + NWAVE * kk;           // 0..47, uniform per wave
-            const int ch = seg / 6, r = seg - ch * 6;
-            const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
-            const float *src = xf + (lane_off_now + (c0 + ch) * hw + r * a.w);
-            float *dst = buf + (ch * 6 + r) * ROW_FLOATS;
-            // LDS address of lane 0's element goes to M0; every lane adds lane * size, and the
-            // instruction's immediate offset applies to the LDS address as well as to the global
-            // one (hence the +4 / -16 corrections for the two halo columns).  Written as
-            // assembly so that the compiler does not track these loads: it would otherwise wait for
-            // them before the record loop (they are waited for explicitly before the next barrier).
-            const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(dst));
-            if (rv) asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst_b));
-            if (rv && (vmask & 0x100u))
-                asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dword %0, off offset:-4" ::"v"(src), "s"(dst_b + 1024u + 4u));
-            if (rv && (vmask & 0x2000u))
-                asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dword %0, off offset:16" ::"v"(src), "s"(dst_b + 1280u - 16u));
+            for (int k = 0; k < 3; ++k) {
+                const int r = 3 * half + k;
+                const float *src = xc + (lane_off_now + r * a.w);
+                const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + r * QUAD_FLOATS));
+                if (cv && ((vmask >> r) & 1u))
+                    asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst_b));
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            const int j = 6 * half + k;
+            const int off = halo_tab[j * 64 + ln];
+            const float *src = xc + off;
+            const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + 6 * QUAD_FLOATS + j * 64));
+            if (cv && off >= 0)
+                asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dword %0, off" ::"v"(src), "s"(dst_b));
         }
     };
-    // generic path (any layout / dtype / width): through registers, with conversion to fp32
+    // generic path (any layout / dtype / width): through registers, with conversion to fp32;
+    // every thread owns SEGS (channel, row) segments of its lane's patch
+    constexpr int SEGS = S::SEGS;
     auto stage_load = [&](int c0, float (&t)[SEGS][6]) {
         const int ln = fresh_lane();
         const int lane_off_now = inv[2 * ln];
         const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
 #pragma unroll
         for (int kk = 0; kk < SEGS; ++kk) {
-            const int seg = wave + NWAVE * kk;
+            const int seg = wave + NW * kk;
             const int ch = seg / 6, r = seg - ch * 6;
             const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
             const int off = LAYOUT == PCONV_NCHW ? lane_off_now + (c0 + ch) * hw + r * a.w
@@ -208,55 +247,51 @@ conv_tiled_kernel(const TiledArgs a)
         const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
 #pragma unroll
         for (int kk = 0; kk < SEGS; ++kk) {
-            const int seg = wave + NWAVE * kk;
+            const int seg = wave + NW * kk;
             const int ch = seg / 6, r = seg - ch * 6;
             const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
             float v[6];
 #pragma unroll
             for (int cc = 0; cc < 6; ++cc) v[cc] = (rv && ((vmask >> (8 + cc)) & 1u)) ? t[kk][cc] : 0.0f;
-            float *dst = buf + (ch * 6 + r) * ROW_FLOATS;
-            *reinterpret_cast<float4 *>(dst + ln * 4) = make_float4(v[1], v[2], v[3], v[4]);
-            dst[256 + ln] = v[0];
-            dst[320 + ln] = v[5];
+            float *cbuf = buf + ch * CHAN_FLOATS;
+            *reinterpret_cast<float4 *>(cbuf + r * QUAD_FLOATS + ln * 4) = make_float4(v[1], v[2], v[3], v[4]);
+            cbuf[(6 + r / 4) * QUAD_FLOATS + ln * 4 + r % 4] = v[0];                    // halo value e = r
+            cbuf[(6 + (6 + r) / 4) * QUAD_FLOATS + ln * 4 + (6 + r) % 4] = v[5];        // halo value e = 6 + r
         }
+    };
+    auto stage = [&](int chunk) {
+        float t[SEGS][6];
+        stage_load(chunk * CH, t);
+        stage_store(chunk * CH, lds + (chunk & 1) * BUF_FLOATS, t);
     };
 
     if (VEC) {
         // zero both staged buffers once (see stage_direct)
 #pragma unroll
-        for (int j = 0; j < 2 * BUF_FLOATS / (NWAVE * 64 * 4); ++j)
-            *reinterpret_cast<float4 *>(lds + (j * NWAVE * 64 + threadIdx.x) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int j = 0; j < 2 * BUF_FLOATS / (NW * 64 * 4); ++j)
+            *reinterpret_cast<float4 *>(lds + (j * NW * 64 + threadIdx.x) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    __syncthreads();                                     // zeroed buffers and the per-lane invariants are visible
+    __syncthreads();                                     // zeroed buffers, tables and counters are visible
 
     // The records of a (filter block, chunk) are contiguous and ordered by channel, so this wave's
     // share of a chunk is the range between two entries of chan_ptr.  The range bounds of up to
     // 64 consecutive chunks sit one per lane in ptr_lo / ptr_hi and are read with v_readlane.
     const int n_chunks = (a.c_in + CH - 1) / CH;
+    const int ptr_max = a.row_len - 1;                   // last entry of a row: end of the block's records
     const uint32_t *__restrict__ ptr_row = a.chan_ptr + size_t(active ? fblk : 0) * a.row_len;
     const int chs = CH >> ks_log2;                       // channels of a chunk per split
     const int sub_lo = ksplit * chs, sub_hi = sub_lo + chs;
     int win_base = 0;
-    uint32_t ptr_lo = ptr_row[min(lane * CH + sub_lo, n_chunks * CH)];
-    uint32_t ptr_hi = ptr_row[min(lane * CH + sub_hi, n_chunks * CH)];
+    uint32_t ptr_lo = ptr_row[min(lane * CH + sub_lo, ptr_max)];
+    uint32_t ptr_hi = ptr_row[min(lane * CH + sub_hi, ptr_max)];
 
-    auto stage = [&](int chunk) {
-        float *buf = lds + (chunk & 1) * BUF_FLOATS;
-        if (VEC) {
-            stage_direct(chunk * CH, buf, wave);
-        } else {
-            float t[SEGS][6];
-            stage_load(chunk * CH, t);
-            stage_store(chunk * CH, buf, t);
-        }
-    };
     // record range of this wave for a chunk, and the fetch of its first batch: lane j gets record
     // j (k0 + k_cnt is the next record or the padding record, always readable)
     auto fetch_records = [&](int chunk, uint32_t &k0, uint32_t &k_cnt, uint32_t &rec_m, float4 &rec_w) {
         if (chunk - win_base > 63) {                     // every 64 chunks: next window of bounds
             win_base = chunk;
-            ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, n_chunks * CH)];
-            ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, n_chunks * CH)];
+            ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, ptr_max)];
+            ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, ptr_max)];
             __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0) here, so that the common path needs no wait
         }
         k0 = __builtin_amdgcn_readlane(ptr_lo, chunk - win_base);
@@ -266,93 +301,139 @@ conv_tiled_kernel(const TiledArgs a)
         rec_w = a.w4[ridx];
     };
 
-    uint32_t k0, k_cnt, rec_m;
-    {
-        float4 rec_w;
-        stage(0);
-        fetch_records(0, k0, k_cnt, rec_m, rec_w);
-        if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
-        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wave's staging loads have landed
-        __syncthreads();
-    }
-
-    for (int chunk = 0; chunk < n_chunks; ++chunk) {
-        // Requests for the next chunk go out first and complete while this chunk is computed:
-        // its inputs (into the other LDS buffer, which every wave has finished reading: they all
-        // passed the barrier at the end of the previous iteration) and this wave's records.
-        const bool more = chunk + 1 < n_chunks;
-        const bool do_ts = a.ts && blockIdx.x == 0 && (threadIdx.x & 63) == 0;
-        if (do_ts) a.ts[(chunk * 16 + wave) * 6 + 0] = __builtin_readcyclecounter();
-        uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
-        float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
-        const bool do_stage = more && !((a.dbg & 1) && chunk >= 1);
-        if (more) {
-            if (!VEC && do_stage) stage(chunk + 1);       // register path: fixed assignment
-            fetch_records(chunk + 1, nk0, nk_cnt, nrec_m, nrec_w);
-        }
-        // the ticket counter of the chunk after next is idle during this iteration: reset it
-        if (VEC && threadIdx.x == 0) tick[chunk & 1] = 0;
-
-        if (do_ts) a.ts[(chunk * 16 + wave) * 6 + 1] = __builtin_readcyclecounter();
-        if (active && !(a.dbg & 2)) {
-            const uint32_t buf_bytes = uint32_t(chunk & 1) * uint32_t(BUF_FLOATS * 4);
-            for (uint32_t base = 0; base < k_cnt; base += BATCH) {
-                if (base > 0) {
-                    // more than BATCH records in this chunk: next batch (the wave's weight block
-                    // is private, and LDS accesses of one wave execute in order)
-                    const uint32_t ridx = k0 + min(base + uint32_t(lane), k_cnt);
-                    rec_m = a.meta[ridx];
-                    const float4 rec_w = a.w4[ridx];
-                    // waiting here, in the rare path, keeps the common path free of a wait for all
-                    // vector-memory loads (which would include the next chunk's staging)
-                    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
-                    if (lane == 0) rec_m |= kMetaFirstOfChannel;   // input registers do not survive between batches
-                    if (lane < BATCH) {
-                        volatile float *wv = wlds + lane * 4;
-                        wv[0] = rec_w.x; wv[1] = rec_w.y; wv[2] = rec_w.z; wv[3] = rec_w.w;
-                    }
+    // ---- the records of one chunk: generated assembly, in batches of up to BATCH records ----
+    auto compute = [&](int chunk, uint32_t k0, uint32_t k_cnt, uint32_t rec_m) {
+        const uint32_t buf_bytes = uint32_t(chunk & 1) * uint32_t(BUF_FLOATS * 4);
+        for (uint32_t base = 0; base < k_cnt; base += BATCH) {
+            if (base > 0) {
+                // more than BATCH records in this chunk (rare): next batch (the wave's weight
+                // block is private, and LDS accesses of one wave execute in order)
+                const uint32_t ridx = k0 + min(base + uint32_t(fresh_lane()), k_cnt);
+                rec_m = a.meta[ridx];
+                const float4 rec_w = a.w4[ridx];
+                // waiting here, in the rare path, keeps the common path free of a wait for all
+                // vector-memory loads (which would include the next chunk's staging)
+                __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
+                if (fresh_lane() == 0) rec_m |= kMetaFirstOfChannel;   // input registers do not survive between batches
+                if (fresh_lane() < BATCH) {
+                    volatile float *wv = wlds + fresh_lane() * 4;
+                    wv[0] = rec_w.x; wv[1] = rec_w.y; wv[2] = rec_w.z; wv[3] = rec_w.w;
                 }
-                const uint32_t nb = __builtin_amdgcn_readfirstlane(min(uint32_t(BATCH), k_cnt - base));
-                asm volatile(
+            }
+            const uint32_t nb = __builtin_amdgcn_readfirstlane(min(uint32_t(BATCH), k_cnt - base));
+            asm volatile(
 #include "pconv_tiled_compute.inc"
-                    : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
-                    : [recm] "v"(rec_m), [va] "v"(lds_base + buf_bytes + uint32_t(fresh_lane()) * 16u),
-                      [vb] "v"(lds_base + buf_bytes + 1024u + uint32_t(fresh_lane()) * 4u), [wa] "s"(wa), [cnt] "s"(nb)
-                    : "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
-                      "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45",
-                      "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57",
-                      "v58", "v59", "v60", "v61", "v62", "v63",
-                      "s84", "s85", "s90", "s91", "s92", "s93", "s94", "s95", "scc");
-                // No "memory" clobber on purpose: it would make the compiler wait for the
-                // global->LDS loads of the next chunk, which are still in flight here and go to
-                // the other buffer.  What the loop reads was written before the barrier above
-                // (or by the volatile store in the batch path).
-            }
+                : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
+                : [recm] "v"(rec_m), [va] "v"(lds_base + buf_bytes + uint32_t(fresh_lane()) * 16u),
+                  [wa] "s"(wa), [first] "s"(0u), [cnt] "s"(nb), [chbfe] "n"(CH == 8 ? 0x30008 : 0x20008)
+                : "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
+                  "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45",
+                  "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57",
+                  "v58", "v59", "v60", "v61", "v62", "v63",
+                  "s84", "s85", "s90", "s91", "s92", "s93", "s94", "s95", "scc");
+            // No "memory" clobber on purpose: it would make the compiler wait for the
+            // global->LDS loads of the next chunk, which may be in flight here and go to the
+            // other buffer.  What the loop reads was published before (barrier / counters), or
+            // written by the volatile stores in the batch path.
         }
+    };
 
-        if (do_ts) { a.ts[(chunk * 16 + wave) * 6 + 2] = __builtin_readcyclecounter(); a.ts[(chunk * 16 + wave) * 6 + 4] = k_cnt; }
-        // stage the next chunk: take units until none is left (the other buffer is free: every
-        // wave passed the barrier at the end of the previous iteration)
-        if (VEC && do_stage) {
-            float *buf = lds + ((chunk + 1) & 1) * BUF_FLOATS;
-            for (;;) {
-                unsigned t = 0;
+    uint32_t k0, k_cnt, rec_m;
+
+    if constexpr (VEC) {
+        // ---- no barrier in this loop: three counters per LDS buffer order the waves ----
+        //   tickets  staging work asked for           (a chunk has UNITS units of half a channel)
+        //   staged   staging units whose data landed  chunk c is readable when staged == UNITS * (c/2 + 1)
+        //   done     waves that finished a chunk      chunk c's buffer may be refilled (with chunk
+        //                                             c + 2) when done == NW * (c/2 + 1)
+        // All counters only grow.  A wave that has finished chunk c stages what is left of chunk
+        // c + 1 (once every wave is done with chunk c - 1, whose buffer it takes), then computes it:
+        // waves may be one chunk apart, so a chunk costs a wave its own records, not the records of
+        // the busiest wave, and the staging falls to the waves with the least to do.  The slowest
+        // wave never waits for a faster one: whatever it needs has been, or can be, produced by
+        // itself.  Waits are bounded (kSpinLimit) so that a mistake here ends in wrong results, not
+        // in a hang.
+        unsigned *tickets = sync_words, *staged = sync_words + 2, *done = sync_words + 4;
+        constexpr int kSpinLimit = 1 << 22;
+        auto wait_ge = [&](unsigned *p, unsigned target) {
+            for (int guard = 0; guard < kSpinLimit; ++guard) {
+                const unsigned v = __builtin_amdgcn_readfirstlane(
+                    __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                if (v >= target) break;
+                __builtin_amdgcn_s_sleep(2);
+            }
+        };
+        // A wave asks for staging work once per chunk, with one atomic add of kClaim: the counter
+        // of a buffer therefore advances by exactly NW * kClaim per chunk, and the first
+        // UNITS / kClaim askers get kClaim units each.  The add for chunk c is issued before the
+        // wave reports chunk c - 1 as done, and LDS operations of a wave execute in order: once
+        // every wave is done with c - 1, all adds for c have been applied, so a fast wave's add
+        // for c + 2 (same counter) cannot get in between.
+        constexpr unsigned kClaim = S::UNITS / 4;
+        auto help_stage = [&](int chunk, bool report_done) {
+            const int p = chunk & 1;
+            unsigned got = 0;
+            if (fresh_lane() == 0) {
+                got = __hip_atomic_fetch_add(&tickets[p], kClaim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                if (report_done)                                       // chunk - 1 used the other buffer
+                    __hip_atomic_fetch_add(&done[p ^ 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+            const unsigned unit0 = __builtin_amdgcn_readfirstlane(got) - unsigned(chunk >> 1) * (NW * kClaim);
+            if (unit0 < unsigned(S::UNITS)) {
+                wait_ge(&done[p], unsigned(chunk >> 1) * NW);          // chunk - 2 is finished: the buffer is free
+                for (unsigned u = 0; u < kClaim; ++u) stage_direct(chunk * CH, lds + p * BUF_FLOATS, int(unit0 + u));
+                __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): the data is in LDS
                 if (fresh_lane() == 0)
-                    t = __hip_atomic_fetch_add(&tick[(chunk + 1) & 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                t = __builtin_amdgcn_readfirstlane(t);
-                if (t >= unsigned(NWAVE)) break;
-                stage_direct((chunk + 1) * CH, buf, int(t));
+                    __hip_atomic_fetch_add(&staged[p], kClaim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        };
+
+        {
+            float4 rec_w;
+            fetch_records(0, k0, k_cnt, rec_m, rec_w);
+            if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
+        }
+        help_stage(0, false);
+        for (int chunk = 0; chunk < n_chunks; ++chunk) {
+            const bool more = chunk + 1 < n_chunks;
+            uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
+            float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (more) fetch_records(chunk + 1, nk0, nk_cnt, nrec_m, nrec_w);   // lands during the records below
+            wait_ge(&staged[chunk & 1], unsigned((chunk >> 1) + 1) * S::UNITS);
+            compute(chunk, k0, k_cnt, rec_m);
+            // every LDS read of this chunk has returned (the record loop waits for its loads)
+            if (more) {
+                if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
+                k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
+                help_stage(chunk + 1, true);
             }
         }
-        // hand over to the next chunk: this wave's weights go to its LDS block (the wave has
-        // finished reading the old ones), its staging loads are waited for, and the barrier
-        // publishes all of it and tells that every wave is done with this chunk's buffer
-        if (more) {
-            if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
-            k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
-            __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
-            if (do_ts) a.ts[(chunk * 16 + wave) * 6 + 3] = __builtin_readcyclecounter();
+        __syncthreads();
+    } else {
+        // ---- register staging path: fixed assignment, one barrier per chunk ----
+        {
+            float4 rec_w;
+            stage(0);
+            fetch_records(0, k0, k_cnt, rec_m, rec_w);
+            if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
             __syncthreads();
+        }
+        for (int chunk = 0; chunk < n_chunks; ++chunk) {
+            // The next chunk goes to the other LDS buffer, which every wave has finished reading
+            // (they all passed the barrier at the end of the previous iteration).
+            const bool more = chunk + 1 < n_chunks;
+            uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
+            float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (more) {
+                stage(chunk + 1);
+                fetch_records(chunk + 1, nk0, nk_cnt, nrec_m, nrec_w);
+            }
+            compute(chunk, k0, k_cnt, rec_m);
+            if (more) {
+                if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
+                k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
+                __syncthreads();
+            }
         }
     }
 
@@ -425,7 +506,41 @@ conv_tiled_kernel(const TiledArgs a)
     }
 }
 
+template <typename T, int LAYOUT, bool VEC, int NW, int CH>
+hipError_t launch_shape(const TiledArgs &a, int64_t wgs, hipStream_t st)
+{
+    static bool attr_done = false;       // (set to the same value by every thread that gets here first)
+    constexpr size_t lds_bytes = Shape<NW, CH>::LDS_BYTES;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_tiled_kernel<T, LAYOUT, VEC, NW, CH>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((conv_tiled_kernel<T, LAYOUT, VEC, NW, CH>), dim3(unsigned(wgs)), dim3(NW * 64), lds_bytes, st, a);
+    return hipGetLastError();
+}
+
+template <int NW, int CH>
+hipError_t launch_any(const TiledArgs &a, int64_t wgs, hipStream_t st, bool vec, int layout, int dtype)
+{
+    if (vec) return launch_shape<float, PCONV_NCHW, true, NW, CH>(a, wgs, st);
+    if (dtype == PCONV_F32)
+        return layout == PCONV_NCHW ? launch_shape<float, PCONV_NCHW, false, NW, CH>(a, wgs, st)
+                                    : launch_shape<float, PCONV_NHWC, false, NW, CH>(a, wgs, st);
+    return layout == PCONV_NCHW ? launch_shape<bf16_t, PCONV_NCHW, false, NW, CH>(a, wgs, st)
+                                : launch_shape<bf16_t, PCONV_NHWC, false, NW, CH>(a, wgs, st);
+}
+
+int g_force_waves = 0, g_force_ks = -1;    // test overrides, see set_tiled_tuning
+
 }  // namespace
+
+void set_tiled_tuning(int waves, int ks_log2)
+{
+    g_force_waves = (waves == 8 || waves == 16) ? waves : 0;
+    g_force_ks = (ks_log2 >= 0 && ks_log2 <= 2) ? ks_log2 : -1;
+}
 
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype)
 {
@@ -448,41 +563,23 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     a.n_patches = n * a.py * a.px;
     a.n_tiles = (a.n_patches + 63) / 64;
     a.n_blocks = h->tiled.num_blocks;
+    a.relu = relu;
+    const bool vec = dtype == PCONV_F32 && layout == PCONV_NCHW && win >= 4;
+    const int64_t tiles8 = int64_t((a.n_tiles + 7) / 8) * 8;
+    // Shape: 16-wave workgroups, one per compute unit, unless the test override asks otherwise.
+    const int nw = g_force_waves ? g_force_waves : 16;
     // channel split: as long as the workgroups would not even fill the 256 compute units once
     a.ks_log2 = 0;
-    while (a.ks_log2 < 2 &&
-           int64_t((a.n_tiles + 7) / 8) * 8 * ((a.n_blocks + (NWAVE >> a.ks_log2) - 1) / (NWAVE >> a.ks_log2)) <= 128)
+    while (a.ks_log2 < 2 && tiles8 * ((a.n_blocks + (nw >> a.ks_log2) - 1) / (nw >> a.ks_log2)) <= 128 * (16 / nw))
         ++a.ks_log2;
-    { const char *e = getenv("PCONV_KS_LOG2"); if (e) a.ks_log2 = atoi(e) & 3; if (a.ks_log2 > 2) a.ks_log2 = 2; }
-    const int fw = NWAVE >> a.ks_log2;
+    if (g_force_ks >= 0) a.ks_log2 = g_force_ks;
+    const int fw = nw >> a.ks_log2;
     a.n_groups = (a.n_blocks + fw - 1) / fw;
-    a.relu = relu;
-    { const char *e = getenv("PCONV_DEBUG_FLAGS"); a.dbg = e ? atoi(e) : 0; }
-    { const char *e = getenv("PCONV_DEBUG_TS"); a.ts = e ? reinterpret_cast<unsigned long long *>(strtoull(e, nullptr, 0)) : nullptr; }
-    const bool vec = dtype == PCONV_F32 && layout == PCONV_NCHW && win >= 4;
-    const int64_t wgs = int64_t((a.n_tiles + 7) / 8) * 8 * a.n_groups;
+    const int64_t wgs = tiles8 * a.n_groups;
     if (wgs > 0x7FFFFFFF) { set_error("pconv_conv2d: too many workgroups"); return PCONV_UNSUPPORTED; }
     hipStream_t st = static_cast<hipStream_t>(stream);
-    hipError_t e = hipSuccess;
-#define PCONV_LAUNCH(T, L, V)                                                                          \
-    do {                                                                                              \
-        static bool attr_done = false;                                                                \
-        if (!attr_done) {                                                                             \
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_tiled_kernel<T, L, V>),      \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(LDS_BYTES));      \
-            attr_done = (e == hipSuccess);                                                            \
-        }                                                                                             \
-        if (e == hipSuccess)                                                                          \
-            hipLaunchKernelGGL((conv_tiled_kernel<T, L, V>), dim3(unsigned(wgs)), dim3(NWAVE * 64), LDS_BYTES, st, a); \
-    } while (0)
-    if (vec) PCONV_LAUNCH(float, PCONV_NCHW, true);
-    else if (dtype == PCONV_F32) {
-        if (layout == PCONV_NCHW) PCONV_LAUNCH(float, PCONV_NCHW, false); else PCONV_LAUNCH(float, PCONV_NHWC, false);
-    } else {
-        if (layout == PCONV_NCHW) PCONV_LAUNCH(bf16_t, PCONV_NCHW, false); else PCONV_LAUNCH(bf16_t, PCONV_NHWC, false);
-    }
-#undef PCONV_LAUNCH
-    if (e == hipSuccess) e = hipGetLastError();
+    const hipError_t e = nw == 16 ? launch_any<16, 8>(a, wgs, st, vec, layout, dtype)
+                                  : launch_any<8, 4>(a, wgs, st, vec, layout, dtype);
     if (e != hipSuccess) {
         set_error(std::string("pconv_conv2d (tiled kernel): ") + hipGetErrorName(e));
         return PCONV_HIP_ERROR;
