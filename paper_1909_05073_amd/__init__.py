@@ -71,7 +71,7 @@ def lib():
     L.pconv_set_kernel_policy.restype = ip
     L.pconv_set_kernel_policy.argtypes = [ip]
     L.pconv_debug_set_tiling.restype = ip
-    L.pconv_debug_set_tiling.argtypes = [ip, ip]
+    L.pconv_debug_set_tiling.argtypes = [ip, ip, ip]
     L.pconv_last_error.restype = C.c_char_p
     L.pconv_last_error.argtypes = []
     _lib = L
@@ -156,8 +156,8 @@ def pconv_set_kernel_policy(policy: int):
     _check(lib().pconv_set_kernel_policy(int(policy)))
 
 
-def pconv_debug_set_tiling(waves: int = 0, ks_log2: int = -1):
-    _check(lib().pconv_debug_set_tiling(int(waves), int(ks_log2)))
+def pconv_debug_set_tiling(waves: int = 0, ks_log2: int = -1, split_units: int = -1):
+    _check(lib().pconv_debug_set_tiling(int(waves), int(ks_log2), int(split_units)))
 
 
 def pconv_debug_export(handle: Handle) -> dict:

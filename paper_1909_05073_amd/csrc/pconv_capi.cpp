@@ -41,7 +41,7 @@ int upload(T *&dst, const T *src, size_t count, int64_t &bytes)
 void release_device(pconv_handle *h)
 {
     void *ptrs[] = {h->d_perm, h->d_row_ptr, h->d_kern, h->d_val_ptr, h->d_vals,
-                    h->d_slot_filter, h->d_chan_ptr, h->d_meta, h->d_w4};
+                    h->d_slot_filter, h->d_chan_ptr, h->d_meta, h->d_w4, h->d_flags};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
 }
@@ -62,9 +62,9 @@ int pconv_set_kernel_policy(int policy)
     return PCONV_OK;
 }
 
-int pconv_debug_set_tiling(int waves, int ks_log2)
+int pconv_debug_set_tiling(int waves, int ks_log2, int split_units)
 {
-    set_tiled_tuning(waves, ks_log2);
+    set_tiled_tuning(waves, ks_log2, split_units);
     return PCONV_OK;
 }
 
@@ -108,6 +108,10 @@ static int pack_impl(const float *w_dense, const uint8_t *pattern_id, const uint
         if (rc == PCONV_OK) rc = upload(h->d_chan_ptr, h->tiled.chan_ptr.data(), h->tiled.chan_ptr.size(), h->device_bytes);
         if (rc == PCONV_OK) rc = upload(h->d_meta, h->tiled.meta.data(), h->tiled.meta.size(), h->device_bytes);
         if (rc == PCONV_OK) rc = upload(h->d_w4, h->tiled.w4.data(), h->tiled.w4.size(), h->device_bytes);
+        if (rc == PCONV_OK) {
+            const std::vector<uint32_t> zeros(size_t(kFlagSlots) * kFlagWords, 0u);
+            rc = upload(h->d_flags, zeros.data(), zeros.size(), h->device_bytes);
+        }
         if (rc != PCONV_OK) { release_device(h); delete h; return rc; }
     } catch (const std::bad_alloc &) {
         if (h) { release_device(h); delete h; }

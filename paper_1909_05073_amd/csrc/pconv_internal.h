@@ -1,6 +1,7 @@
 // Internal declarations shared by the host packer, the kernels' launchers and the C ABI.
 #pragma once
 
+#include <atomic>
 #include <cstdint>
 #include <string>
 #include <vector>
@@ -8,6 +9,8 @@
 #include "pconv.h"
 
 namespace pconv {
+
+constexpr int kFlagSlots = 64, kFlagWords = 1024;
 
 // Thread-local message for pconv_last_error().
 void set_error(const std::string &msg);
@@ -57,6 +60,11 @@ struct pconv_handle {
     uint32_t *d_chan_ptr = nullptr;
     uint32_t *d_meta = nullptr;
     float    *d_w4 = nullptr;
+    // Hand-over words of the tiled kernel: workgroups that share a unit of work signal each other
+    // through kFlagWords words; every call takes the next of kFlagSlots such rows and a fresh
+    // value, so calls that overlap on different streams do not see each other's signals.
+    uint32_t *d_flags = nullptr;     // [kFlagSlots][kFlagWords], zero at start
+    mutable std::atomic<uint32_t> calls{0};
 };
 
 namespace pconv {
@@ -75,8 +83,9 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
                       int hin, int win, int stride, int layout, int dtype, int relu, void *stream);
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype);
 // Test override of the tiled kernel's launch choices: waves per workgroup (8 or 16, anything else =
-// automatic) and log2 of the channel split inside a workgroup (0..2, anything else = automatic).
-void set_tiled_tuning(int waves, int ks_log2);
+// automatic), log2 of the channel split inside a workgroup (0..2, anything else = automatic), and
+// whether workgroups may share a unit of work (0 / 1, anything else = automatic).
+void set_tiled_tuning(int waves, int ks_log2, int split_units);
 int launch_maxpool2x2(const void *x, void *y, int n, int c, int h, int w, int layout, int dtype,
                       void *stream);
 

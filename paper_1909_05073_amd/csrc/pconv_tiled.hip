@@ -21,6 +21,7 @@
 // straight-line code with compile-time register indices (paper: per-pattern generated code, one
 // branch per kernel instead of per weight), reached by one computed jump per record.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <cstdlib>
 
 #include "pconv_internal.h"
@@ -80,6 +81,11 @@ struct TiledArgs {
     int n_patches, n_tiles, n_groups, n_blocks;
     int relu;
     int ks_log2;                // log2 of the channel split inside a workgroup (0, 1 or 2)
+    int n_units;                // n_tiles * n_groups: (tile, filter group) pairs
+    int n_chunks;               // chunks of CH input channels
+    int split_units;            // 1: a workgroup's share of the work may begin and end inside a unit
+    uint32_t *flags;            // [gridDim.x] hand-over words of this call (split_units only)
+    uint32_t epoch;             // value that marks a hand-over word as set by this call (never 0)
 };
 
 template <typename T, int LAYOUT>
@@ -89,9 +95,25 @@ __device__ __forceinline__ size_t act_at(int n, int c, int y, int x, int C, int 
     return ((size_t(n) * H + y) * W + x) * C + c;
 }
 
+// How the work is spread over the workgroups.  A unit is one (tile of 64 patches, group of 4 * FW
+// filters) pair walked over all chunks of input channels; one unit step ("iteration") is one chunk
+// of one unit.  The workgroups whose ids are equal mod 8 run on one XCD (one L2); set s gets the
+// tiles s, s + 8, ... with all their filter groups, tile-major, so that the filter groups of a tile
+// read its input through the same L2 and the eight XCDs work on neighbouring tiles at any time.
+// Inside a set the iterations are dealt out evenly:
+//   split_units == 0   in whole units (a workgroup gets zero or more of them);
+//   split_units == 1   as equal contiguous ranges of iterations, so a unit may be shared by two
+//                      or more consecutive workgroups of the set, each taking a range of its chunks.
+// The workgroups that share a unit add their partial sums through the output tensor itself, in
+// order of their ids: each one adds what its predecessor left there, and either leaves the new
+// sum for its successor (raw, no bias) or, if it holds the unit's last chunk, finishes the
+// outputs.  A workgroup runs the piece it must hand on first and the piece it takes over last;
+// the hardware starts workgroups in order of their ids, so whatever a workgroup waits for
+// belongs to a workgroup that has already started and handed over at its very beginning.
+//
 // VEC: fp32 NCHW tensors at least 4 wide move the four centre columns of a patch row (and the four
 // outputs of a row) with one 128-bit access; the inputs go from global memory straight to LDS.
-template <typename T, int LAYOUT, bool VEC, int NW, int CH>
+template <typename T, int LAYOUT, bool VEC, int NW, int CH, bool SPLIT>
 __global__ void __launch_bounds__(NW * 64, 4)   // 4 waves per SIMD: at most 128 VGPRs
 conv_tiled_kernel(const TiledArgs a)
 {
@@ -99,44 +121,19 @@ conv_tiled_kernel(const TiledArgs a)
     constexpr int BUF_FLOATS = S::BUF_FLOATS;
     extern __shared__ __attribute__((aligned(16))) float lds[];
 
-    // workgroup id -> (tile, filter group); the groups of one tile share an XCD (ids equal mod 8)
-    const int id = blockIdx.x;
-    const int xcd = id & 7, q = id >> 3;
-    const int tile = (q / a.n_groups) * 8 + xcd, group = q % a.n_groups;
-    if (tile >= a.n_tiles) return;
-
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // The waves are FW filter blocks x KS channel splits (KS = 1 for large layers).  With KS > 1
     // the waves of one filter block share its filters, each takes CH / KS of the channels of every
-    // chunk, and the partial sums are added through LDS at the end in a fixed order: layers with
-    // few patches then still fill the machine.
+    // chunk, and the partial sums are added through LDS at the end in a fixed order.
     const int ks_log2 = a.ks_log2;
     const int fw = NW >> ks_log2;                        // filter blocks per workgroup
     const int ksplit = wave / fw;                        // this wave's channel split
-    const int fblk = group * fw + (wave - ksplit * fw);
-    const bool active = fblk < a.n_blocks;
+    const int chs = CH >> ks_log2;                       // channels of a chunk per split
+    const int sub_lo = ksplit * chs, sub_hi = sub_lo + chs;
 
     const T *__restrict__ x = static_cast<const T *>(a.x);
     T *__restrict__ y = static_cast<T *>(a.y);
-
-    // this lane's patch
-    const int pidx = tile * 64 + lane;
-    const bool pvalid = pidx < a.n_patches;
-    const int per_img = a.py * a.px;
-    const int n = pvalid ? pidx / per_img : 0;
-    const int prem = pvalid ? pidx - n * per_img : 0;
-    // VEC: the last patch of a row is shifted left so that it ends at the image edge (it then
-    // overlaps its neighbour and both compute identical values for the shared columns): the four
-    // centre columns of a patch row are then always inside the image.
-    const int y0 = (prem / a.px) * 4;
-    const int x0 = VEC ? min((prem % a.px) * 4, a.w - 4) : (prem % a.px) * 4;
-
-    // accumulators: slot s, output (row i, column k) of the patch = acc[s][4 * i + k].  The record
-    // loop is assembly with a fixed register map, so each vector is pinned to its registers there.
-    v16f acc[FB];
-#pragma unroll
-    for (int s = 0; s < FB; ++s) acc[s] = 0.0f;
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
     // (Per-lane values are deliberately recomputed where they are used, from a lane id the
     // compiler cannot see through: only a few vector registers may stay live across the record
@@ -144,402 +141,508 @@ conv_tiled_kernel(const TiledArgs a)
     auto fresh_lane = [&]() { int l = threadIdx.x & 63; asm volatile("" : "+v"(l)); return l; };
     float *wlds = lds + S::OFF_W + wave * (BATCH * 4);   // this wave's weight block
     const uint32_t wa = lds_base + uint32_t(S::OFF_W + wave * (BATCH * 4)) * 4u;
-
-    // ---- staging ----
-    // Loads are branch-free: an out-of-image element is not loaded (VEC) or reads element 0 of the
-    // tensor and is replaced by zero when the segment is written to LDS.  What is valid for this
-    // lane does not change from chunk to chunk and is kept as one bit mask: bits 0-5 input rows
-    // y0-1 .. y0+4, bits 8-13 input columns x0-1 .. x0+4.
-    uint32_t vmask0 = 0;
-#pragma unroll
-    for (int r = 0; r < 6; ++r) {
-        const int iy = y0 - 1 + r, ix = x0 - 1 + r;
-        if (pvalid && iy >= 0 && iy < a.h) vmask0 |= 1u << r;
-        if (ix >= 0 && ix < a.w) vmask0 |= 0x100u << r;
-    }
-    const int hw = a.h * a.w;
-    // element offset of (channel 0 of the chunk, row y0-1, column x0) follows from c0; tensors have
-    // fewer than 2^31 elements, so 32-bit offsets suffice (they are only used where valid)
-    const int lane_off0 = LAYOUT == PCONV_NCHW ? (n * a.c_in * a.h + (y0 - 1)) * a.w + x0
-                                              : ((n * a.h + (y0 - 1)) * a.w + x0) * a.c_in;
-    // all waves work on the same 64 patches: the per-lane invariants live in LDS, one copy
     int *inv = reinterpret_cast<int *>(lds + S::OFF_INV);
     unsigned *sync_words = reinterpret_cast<unsigned *>(lds + S::OFF_SYNC);
-    if (threadIdx.x < SYNC_WORDS) sync_words[threadIdx.x] = 0;
-    if (wave == 0) { inv[2 * lane] = lane_off0; inv[2 * lane + 1] = int(vmask0); }
-    // VEC path: the twelve halo values of a patch are fetched by twelve one-word loads per channel,
-    // each of which fills 64 consecutive words of the halo blocks: word i of load j belongs to patch
-    // 16 * (j % 4) + i / 4 and is its halo value e = 4 * (j / 4) + i % 4.  The element offset of that
-    // value in channel 0 (or -1 outside the image) is the same for every chunk: tabulated once.
     int *halo_tab = reinterpret_cast<int *>(lds + S::OFF_HALO);
-    if (VEC) {
-        for (int t = threadIdx.x; t < HALO_TAB_WORDS; t += NW * 64) {
-            const int j = t >> 6, i = t & 63;
-            const int e = 4 * (j >> 2) + (i & 3);
-            const int pidx_h = tile * 64 + 16 * (j & 3) + (i >> 2);
-            const int n_h = pidx_h / per_img, prem_h = pidx_h - n_h * per_img;
-            const int iy = (prem_h / a.px) * 4 - 1 + (e < 6 ? e : e - 6);
-            const int xh = min((prem_h % a.px) * 4, a.w - 4);
-            const int ix = e < 6 ? xh - 1 : xh + 4;
-            const bool ok = pidx_h < a.n_patches && iy >= 0 && iy < a.h && ix >= 0 && ix < a.w;
-            halo_tab[t] = ok ? (n_h * a.c_in * a.h + iy) * a.w + ix : -1;
-        }
+    const int per_img = a.py * a.px;
+    const int hw = a.h * a.w;
+    const int n_chunks = a.n_chunks;
+
+    // ---- this workgroup's range of iterations ----
+    const int set = blockIdx.x & 7, j_in_set = blockIdx.x >> 3;
+    const int set_units = ((a.n_tiles - set + 7) >> 3) * a.n_groups;         // tiles set, set + 8, ...
+    // SPLIT: iteration = (unit of the set) * n_chunks + chunk; otherwise one whole unit per workgroup
+    int ua = j_in_set, ub = j_in_set, head_c0 = 0, tail_c1 = n_chunks;
+    if constexpr (SPLIT) {
+        const int wgs_in_set = (int(gridDim.x) - set + 7) >> 3;
+        const int64_t iters = int64_t(set_units) * n_chunks;
+        const int64_t takers = iters < wgs_in_set ? iters : wgs_in_set;       // nobody gets an empty range in between
+        if (j_in_set >= takers) return;
+        const int64_t it0 = iters * j_in_set / takers, it1 = iters * (j_in_set + 1) / takers;
+        ua = int(it0 / n_chunks); ub = int((it1 - 1) / n_chunks);            // first and last unit touched
+        head_c0 = int(it0 - int64_t(ua) * n_chunks);                         // > 0: unit ua begins elsewhere
+        tail_c1 = int(it1 - int64_t(ub) * n_chunks);                         // < n_chunks: unit ub ends elsewhere
+    } else {
+        if (j_in_set >= set_units) return;
     }
-    // VEC path: global -> LDS directly, no registers and no vector ALU work.  Lanes whose row (or
-    // halo value) lies outside the image are masked off; their LDS words were zeroed once at
-    // kernel start and are never written, so they stay zero for every chunk.
-    // One unit of staging work = half a channel: three rows and six halo loads.
-    auto stage_direct = [&](int c0, float *buf, int unit) {
-        const int ln = fresh_lane();
-        const int ch = unit >> 1, half = unit & 1;
-        const bool cv = c0 + ch < a.c_in;
-        const float *xc = reinterpret_cast<const float *>(x) + (c0 + ch) * hw;
-        float *cbuf = buf + ch * CHAN_FLOATS;
-        // The LDS address of lane 0's element goes to M0 and every lane adds lane * size.  Written
-        // as assembly so that the compiler does not track these loads: it would otherwise wait for
-        // them before the record loop (they are waited for explicitly before they are published).
-        {
+    const bool has_head = head_c0 > 0, has_tail = tail_c1 < n_chunks;
+    const bool one_piece = ua == ub;
+    // order: the piece to hand on, whole units, the piece taken over
+    const int first_whole = has_head ? ua + 1 : ua, last_whole = has_tail ? ub - 1 : ub;
+    const int n_whole = last_whole >= first_whole ? last_whole - first_whole + 1 : 0;
+    const int n_pieces = SPLIT ? (has_tail ? 1 : 0) + n_whole + ((has_head && !(one_piece && has_tail)) ? 1 : 0) : 1;
+
+    for (int piece = 0; piece < n_pieces; ++piece) {
+        int unit, c_begin = 0, c_end = n_chunks;
+        if (has_tail && piece == 0) { unit = ub; c_end = tail_c1; if (one_piece) c_begin = head_c0; }
+        else if (piece - (has_tail ? 1 : 0) < n_whole) unit = first_whole + piece - (has_tail ? 1 : 0);
+        else { unit = ua; c_begin = head_c0; }
+        const bool takes_over = SPLIT && c_begin > 0, hands_on = SPLIT && c_end < n_chunks;
+        const int tile = (unit / a.n_groups) * 8 + set, group = unit % a.n_groups;
+        const int fblk = group * fw + (wave - ksplit * fw);
+        const bool active = fblk < a.n_blocks;
+
+        if (SPLIT) __syncthreads();                      // every wave has left the previous piece: LDS is free
+
+        // this lane's patch
+        const int pidx = tile * 64 + lane;
+        const bool pvalid = pidx < a.n_patches;
+        const int n = pvalid ? pidx / per_img : 0;
+        const int prem = pvalid ? pidx - n * per_img : 0;
+        // VEC: the last patch of a row is shifted left so that it ends at the image edge (it then
+        // overlaps its neighbour and both compute identical values for the shared columns): the four
+        // centre columns of a patch row are then always inside the image.
+        const int y0 = (prem / a.px) * 4;
+        const int x0 = VEC ? min((prem % a.px) * 4, a.w - 4) : (prem % a.px) * 4;
+
+        // accumulators: slot s, output (row i, column k) of the patch = acc[s][4 * i + k].  The record
+        // loop is assembly with a fixed register map, so each vector is pinned to its registers there.
+        v16f acc[FB];
+#pragma unroll
+        for (int s = 0; s < FB; ++s) acc[s] = 0.0f;
+
+        // ---- staging ----
+        // Loads are branch-free: an out-of-image element is not loaded (VEC) or reads element 0 of the
+        // tensor and is replaced by zero when the segment is written to LDS.  What is valid for this
+        // lane does not change from chunk to chunk and is kept as one bit mask: bits 0-5 input rows
+        // y0-1 .. y0+4, bits 8-13 input columns x0-1 .. x0+4.
+        uint32_t vmask0 = 0;
+#pragma unroll
+        for (int r = 0; r < 6; ++r) {
+            const int iy = y0 - 1 + r, ix = x0 - 1 + r;
+            if (pvalid && iy >= 0 && iy < a.h) vmask0 |= 1u << r;
+            if (ix >= 0 && ix < a.w) vmask0 |= 0x100u << r;
+        }
+        // element offset of (channel 0 of the chunk, row y0-1, column x0) follows from c0; tensors have
+        // fewer than 2^31 elements, so 32-bit offsets suffice (they are only used where valid)
+        const int lane_off0 = LAYOUT == PCONV_NCHW ? (n * a.c_in * a.h + (y0 - 1)) * a.w + x0
+                                                  : ((n * a.h + (y0 - 1)) * a.w + x0) * a.c_in;
+        // all waves work on the same 64 patches: the per-lane invariants live in LDS, one copy
+        if (threadIdx.x < SYNC_WORDS) sync_words[threadIdx.x] = 0;
+        if (wave == 0) { inv[2 * lane] = lane_off0; inv[2 * lane + 1] = int(vmask0); }
+        // VEC path: the twelve halo values of a patch are fetched by twelve one-word loads per channel,
+        // each of which fills 64 consecutive words of the halo blocks: word i of load j belongs to patch
+        // 16 * (j % 4) + i / 4 and is its halo value e = 4 * (j / 4) + i % 4.  The element offset of that
+        // value in channel 0 (or -1 outside the image) is the same for every chunk: tabulated once.
+        if (VEC) {
+            for (int t = threadIdx.x; t < HALO_TAB_WORDS; t += NW * 64) {
+                const int j = t >> 6, i = t & 63;
+                const int e = 4 * (j >> 2) + (i & 3);
+                const int pidx_h = tile * 64 + 16 * (j & 3) + (i >> 2);
+                const int n_h = pidx_h / per_img, prem_h = pidx_h - n_h * per_img;
+                const int iy = (prem_h / a.px) * 4 - 1 + (e < 6 ? e : e - 6);
+                const int xh = min((prem_h % a.px) * 4, a.w - 4);
+                const int ix = e < 6 ? xh - 1 : xh + 4;
+                const bool ok = pidx_h < a.n_patches && iy >= 0 && iy < a.h && ix >= 0 && ix < a.w;
+                halo_tab[t] = ok ? (n_h * a.c_in * a.h + iy) * a.w + ix : -1;
+            }
+        }
+        // VEC path: global -> LDS directly, no registers and no vector ALU work.  Lanes whose row (or
+        // halo value) lies outside the image are masked off; their LDS words are zeroed once per
+        // piece and never written, so they stay zero for every chunk.
+        // One unit of staging work = half a channel: three rows and six halo loads.
+        auto stage_direct = [&](int c0, float *buf, int sunit) {
+            const int ln = fresh_lane();
+            const int ch = sunit >> 1, half = sunit & 1;
+            const bool cv = c0 + ch < a.c_in;
+            const float *xc = reinterpret_cast<const float *>(x) + (c0 + ch) * hw;
+            float *cbuf = buf + ch * CHAN_FLOATS;
+            // The LDS address of lane 0's element goes to M0 and every lane adds lane * size.  Written
+            // as assembly so that the compiler does not track these loads: it would otherwise wait for
+            // them before the record loop (they are waited for explicitly before they are published).
+            {
+                const int lane_off_now = inv[2 * ln];
+                const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
+#pragma unroll
+                for (int k = 0; k < 3; ++k) {
+                    const int r = 3 * half + k;
+                    const float *src = xc + (lane_off_now + r * a.w);
+                    const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + r * QUAD_FLOATS));
+                    if (cv && ((vmask >> r) & 1u))
+                        asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst_b));
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 6; ++k) {
+                const int j = 6 * half + k;
+                const int off = halo_tab[j * 64 + ln];
+                const float *src = xc + off;
+                const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + 6 * QUAD_FLOATS + j * 64));
+                if (cv && off >= 0)
+                    asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dword %0, off" ::"v"(src), "s"(dst_b));
+            }
+        };
+        // generic path (any layout / dtype / width): through registers, with conversion to fp32;
+        // every thread owns SEGS (channel, row) segments of its lane's patch
+        constexpr int SEGS = S::SEGS;
+        auto stage_load = [&](int c0, float (&t)[SEGS][6]) {
+            const int ln = fresh_lane();
             const int lane_off_now = inv[2 * ln];
             const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
 #pragma unroll
-            for (int k = 0; k < 3; ++k) {
-                const int r = 3 * half + k;
-                const float *src = xc + (lane_off_now + r * a.w);
-                const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + r * QUAD_FLOATS));
-                if (cv && ((vmask >> r) & 1u))
-                    asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst_b));
-            }
-        }
+            for (int kk = 0; kk < SEGS; ++kk) {
+                const int seg = wave + NW * kk;
+                const int ch = seg / 6, r = seg - ch * 6;
+                const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
+                const int off = LAYOUT == PCONV_NCHW ? lane_off_now + (c0 + ch) * hw + r * a.w
+                                                     : lane_off_now + r * a.w * a.c_in + (c0 + ch);
 #pragma unroll
-        for (int k = 0; k < 6; ++k) {
-            const int j = 6 * half + k;
-            const int off = halo_tab[j * 64 + ln];
-            const float *src = xc + off;
-            const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + 6 * QUAD_FLOATS + j * 64));
-            if (cv && off >= 0)
-                asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dword %0, off" ::"v"(src), "s"(dst_b));
-        }
-    };
-    // generic path (any layout / dtype / width): through registers, with conversion to fp32;
-    // every thread owns SEGS (channel, row) segments of its lane's patch
-    constexpr int SEGS = S::SEGS;
-    auto stage_load = [&](int c0, float (&t)[SEGS][6]) {
-        const int ln = fresh_lane();
-        const int lane_off_now = inv[2 * ln];
-        const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
-#pragma unroll
-        for (int kk = 0; kk < SEGS; ++kk) {
-            const int seg = wave + NW * kk;
-            const int ch = seg / 6, r = seg - ch * 6;
-            const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
-            const int off = LAYOUT == PCONV_NCHW ? lane_off_now + (c0 + ch) * hw + r * a.w
-                                                 : lane_off_now + r * a.w * a.c_in + (c0 + ch);
-#pragma unroll
-            for (int cc = 0; cc < 6; ++cc) {
-                const bool ok = rv && ((vmask >> (8 + cc)) & 1u);
-                const int e = LAYOUT == PCONV_NCHW ? off + (cc - 1) : off + (cc - 1) * a.c_in;
-                t[kk][cc] = ld_act(x, size_t(ok ? e : 0));
-            }
-        }
-    };
-    auto stage_store = [&](int c0, float *buf, const float (&t)[SEGS][6]) {
-        const int ln = fresh_lane();
-        const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
-#pragma unroll
-        for (int kk = 0; kk < SEGS; ++kk) {
-            const int seg = wave + NW * kk;
-            const int ch = seg / 6, r = seg - ch * 6;
-            const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
-            float v[6];
-#pragma unroll
-            for (int cc = 0; cc < 6; ++cc) v[cc] = (rv && ((vmask >> (8 + cc)) & 1u)) ? t[kk][cc] : 0.0f;
-            float *cbuf = buf + ch * CHAN_FLOATS;
-            *reinterpret_cast<float4 *>(cbuf + r * QUAD_FLOATS + ln * 4) = make_float4(v[1], v[2], v[3], v[4]);
-            cbuf[(6 + r / 4) * QUAD_FLOATS + ln * 4 + r % 4] = v[0];                    // halo value e = r
-            cbuf[(6 + (6 + r) / 4) * QUAD_FLOATS + ln * 4 + (6 + r) % 4] = v[5];        // halo value e = 6 + r
-        }
-    };
-    auto stage = [&](int chunk) {
-        float t[SEGS][6];
-        stage_load(chunk * CH, t);
-        stage_store(chunk * CH, lds + (chunk & 1) * BUF_FLOATS, t);
-    };
-
-    if (VEC) {
-        // zero both staged buffers once (see stage_direct)
-#pragma unroll
-        for (int j = 0; j < 2 * BUF_FLOATS / (NW * 64 * 4); ++j)
-            *reinterpret_cast<float4 *>(lds + (j * NW * 64 + threadIdx.x) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-    __syncthreads();                                     // zeroed buffers, tables and counters are visible
-
-    // The records of a (filter block, chunk) are contiguous and ordered by channel, so this wave's
-    // share of a chunk is the range between two entries of chan_ptr.  The range bounds of up to
-    // 64 consecutive chunks sit one per lane in ptr_lo / ptr_hi and are read with v_readlane.
-    const int n_chunks = (a.c_in + CH - 1) / CH;
-    const int ptr_max = a.row_len - 1;                   // last entry of a row: end of the block's records
-    const uint32_t *__restrict__ ptr_row = a.chan_ptr + size_t(active ? fblk : 0) * a.row_len;
-    const int chs = CH >> ks_log2;                       // channels of a chunk per split
-    const int sub_lo = ksplit * chs, sub_hi = sub_lo + chs;
-    int win_base = 0;
-    uint32_t ptr_lo = ptr_row[min(lane * CH + sub_lo, ptr_max)];
-    uint32_t ptr_hi = ptr_row[min(lane * CH + sub_hi, ptr_max)];
-
-    // record range of this wave for a chunk, and the fetch of its first batch: lane j gets record
-    // j (k0 + k_cnt is the next record or the padding record, always readable)
-    auto fetch_records = [&](int chunk, uint32_t &k0, uint32_t &k_cnt, uint32_t &rec_m, float4 &rec_w) {
-        if (chunk - win_base > 63) {                     // every 64 chunks: next window of bounds
-            win_base = chunk;
-            ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, ptr_max)];
-            ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, ptr_max)];
-            __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0) here, so that the common path needs no wait
-        }
-        k0 = __builtin_amdgcn_readlane(ptr_lo, chunk - win_base);
-        k_cnt = active ? __builtin_amdgcn_readlane(ptr_hi, chunk - win_base) - k0 : 0u;
-        const uint32_t ridx = k0 + min(uint32_t(lane), k_cnt);
-        rec_m = a.meta[ridx];
-        rec_w = a.w4[ridx];
-    };
-
-    // ---- the records of one chunk: generated assembly, in batches of up to BATCH records ----
-    auto compute = [&](int chunk, uint32_t k0, uint32_t k_cnt, uint32_t rec_m) {
-        const uint32_t buf_bytes = uint32_t(chunk & 1) * uint32_t(BUF_FLOATS * 4);
-        for (uint32_t base = 0; base < k_cnt; base += BATCH) {
-            if (base > 0) {
-                // more than BATCH records in this chunk (rare): next batch (the wave's weight
-                // block is private, and LDS accesses of one wave execute in order)
-                const uint32_t ridx = k0 + min(base + uint32_t(fresh_lane()), k_cnt);
-                rec_m = a.meta[ridx];
-                const float4 rec_w = a.w4[ridx];
-                // waiting here, in the rare path, keeps the common path free of a wait for all
-                // vector-memory loads (which would include the next chunk's staging)
-                __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
-                if (fresh_lane() == 0) rec_m |= kMetaFirstOfChannel;   // input registers do not survive between batches
-                if (fresh_lane() < BATCH) {
-                    volatile float *wv = wlds + fresh_lane() * 4;
-                    wv[0] = rec_w.x; wv[1] = rec_w.y; wv[2] = rec_w.z; wv[3] = rec_w.w;
+                for (int cc = 0; cc < 6; ++cc) {
+                    const bool ok = rv && ((vmask >> (8 + cc)) & 1u);
+                    const int e = LAYOUT == PCONV_NCHW ? off + (cc - 1) : off + (cc - 1) * a.c_in;
+                    t[kk][cc] = ld_act(x, size_t(ok ? e : 0));
                 }
             }
-            const uint32_t nb = __builtin_amdgcn_readfirstlane(min(uint32_t(BATCH), k_cnt - base));
-            asm volatile(
+        };
+        auto stage_store = [&](int c0, float *buf, const float (&t)[SEGS][6]) {
+            const int ln = fresh_lane();
+            const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
+#pragma unroll
+            for (int kk = 0; kk < SEGS; ++kk) {
+                const int seg = wave + NW * kk;
+                const int ch = seg / 6, r = seg - ch * 6;
+                const bool rv = ((vmask >> r) & 1u) && (c0 + ch < a.c_in);
+                float v[6];
+#pragma unroll
+                for (int cc = 0; cc < 6; ++cc) v[cc] = (rv && ((vmask >> (8 + cc)) & 1u)) ? t[kk][cc] : 0.0f;
+                float *cbuf = buf + ch * CHAN_FLOATS;
+                *reinterpret_cast<float4 *>(cbuf + r * QUAD_FLOATS + ln * 4) = make_float4(v[1], v[2], v[3], v[4]);
+                cbuf[(6 + r / 4) * QUAD_FLOATS + ln * 4 + r % 4] = v[0];                    // halo value e = r
+                cbuf[(6 + (6 + r) / 4) * QUAD_FLOATS + ln * 4 + (6 + r) % 4] = v[5];        // halo value e = 6 + r
+            }
+        };
+        // (rel = chunk index relative to the piece; it selects the LDS buffer)
+        auto stage = [&](int rel) {
+            float t[SEGS][6];
+            stage_load((c_begin + rel) * CH, t);
+            stage_store((c_begin + rel) * CH, lds + (rel & 1) * BUF_FLOATS, t);
+        };
+
+        if (VEC) {
+            // zero both staged buffers (see stage_direct)
+#pragma unroll
+            for (int j = 0; j < 2 * BUF_FLOATS / (NW * 64 * 4); ++j)
+                *reinterpret_cast<float4 *>(lds + (j * NW * 64 + threadIdx.x) * 4) = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        __syncthreads();                                 // zeroed buffers, tables and counters are visible
+
+        // The records of a (filter block, chunk) are contiguous and ordered by channel, so this wave's
+        // share of a chunk is the range between two entries of chan_ptr.  The range bounds of up to
+        // 64 consecutive chunks sit one per lane in ptr_lo / ptr_hi and are read with v_readlane.
+        const int ptr_max = a.row_len - 1;               // last entry of a row: end of the block's records
+        const uint32_t *__restrict__ ptr_row = a.chan_ptr + size_t(active ? fblk : 0) * a.row_len;
+        int win_base = c_begin;
+        uint32_t ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, ptr_max)];
+        uint32_t ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, ptr_max)];
+
+        // record range of this wave for a chunk, and the fetch of its first batch: lane j gets record
+        // j (k0 + k_cnt is the next record or the padding record, always readable)
+        auto fetch_records = [&](int chunk, uint32_t &k0, uint32_t &k_cnt, uint32_t &rec_m, float4 &rec_w) {
+            if (chunk - win_base > 63) {                 // every 64 chunks: next window of bounds
+                win_base = chunk;
+                ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, ptr_max)];
+                ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, ptr_max)];
+                __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0) here, so that the common path needs no wait
+            }
+            k0 = __builtin_amdgcn_readlane(ptr_lo, chunk - win_base);
+            k_cnt = active ? __builtin_amdgcn_readlane(ptr_hi, chunk - win_base) - k0 : 0u;
+            const uint32_t ridx = k0 + min(uint32_t(lane), k_cnt);
+            rec_m = a.meta[ridx];
+            rec_w = a.w4[ridx];
+        };
+
+        // ---- the records of one chunk: generated assembly, in batches of up to BATCH records ----
+        auto compute = [&](int rel, uint32_t k0, uint32_t k_cnt, uint32_t rec_m) {
+            const uint32_t buf_bytes = uint32_t(rel & 1) * uint32_t(BUF_FLOATS * 4);
+            for (uint32_t base = 0; base < k_cnt; base += BATCH) {
+                if (base > 0) {
+                    // more than BATCH records in this chunk (rare): next batch (the wave's weight
+                    // block is private, and LDS accesses of one wave execute in order)
+                    const uint32_t ridx = k0 + min(base + uint32_t(fresh_lane()), k_cnt);
+                    rec_m = a.meta[ridx];
+                    const float4 rec_w = a.w4[ridx];
+                    // waiting here, in the rare path, keeps the common path free of a wait for all
+                    // vector-memory loads (which would include the next chunk's staging)
+                    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
+                    if (fresh_lane() == 0) rec_m |= kMetaFirstOfChannel;   // input registers do not survive between batches
+                    if (fresh_lane() < BATCH) {
+                        volatile float *wv = wlds + fresh_lane() * 4;
+                        wv[0] = rec_w.x; wv[1] = rec_w.y; wv[2] = rec_w.z; wv[3] = rec_w.w;
+                    }
+                }
+                const uint32_t nb = __builtin_amdgcn_readfirstlane(min(uint32_t(BATCH), k_cnt - base));
+                asm volatile(
 #include "pconv_tiled_compute.inc"
-                : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
-                : [recm] "v"(rec_m), [va] "v"(lds_base + buf_bytes + uint32_t(fresh_lane()) * 16u),
-                  [wa] "s"(wa), [first] "s"(0u), [cnt] "s"(nb), [chbfe] "n"(CH == 8 ? 0x30008 : 0x20008)
-                : "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
-                  "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45",
-                  "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57",
-                  "v58", "v59", "v60", "v61", "v62", "v63",
-                  "s84", "s85", "s90", "s91", "s92", "s93", "s94", "s95", "scc");
-            // No "memory" clobber on purpose: it would make the compiler wait for the
-            // global->LDS loads of the next chunk, which may be in flight here and go to the
-            // other buffer.  What the loop reads was published before (barrier / counters), or
-            // written by the volatile stores in the batch path.
-        }
-    };
-
-    uint32_t k0, k_cnt, rec_m;
-
-    if constexpr (VEC) {
-        // ---- no barrier in this loop: three counters per LDS buffer order the waves ----
-        //   tickets  staging work asked for           (a chunk has UNITS units of half a channel)
-        //   staged   staging units whose data landed  chunk c is readable when staged == UNITS * (c/2 + 1)
-        //   done     waves that finished a chunk      chunk c's buffer may be refilled (with chunk
-        //                                             c + 2) when done == NW * (c/2 + 1)
-        // All counters only grow.  A wave that has finished chunk c stages what is left of chunk
-        // c + 1 (once every wave is done with chunk c - 1, whose buffer it takes), then computes it:
-        // waves may be one chunk apart, so a chunk costs a wave its own records, not the records of
-        // the busiest wave, and the staging falls to the waves with the least to do.  The slowest
-        // wave never waits for a faster one: whatever it needs has been, or can be, produced by
-        // itself.  Waits are bounded (kSpinLimit) so that a mistake here ends in wrong results, not
-        // in a hang.
-        unsigned *tickets = sync_words, *staged = sync_words + 2, *done = sync_words + 4;
-        constexpr int kSpinLimit = 1 << 22;
-        auto wait_ge = [&](unsigned *p, unsigned target) {
-            for (int guard = 0; guard < kSpinLimit; ++guard) {
-                const unsigned v = __builtin_amdgcn_readfirstlane(
-                    __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                if (v >= target) break;
-                __builtin_amdgcn_s_sleep(2);
-            }
-        };
-        // A wave asks for staging work once per chunk, with one atomic add of kClaim: the counter
-        // of a buffer therefore advances by exactly NW * kClaim per chunk, and the first
-        // UNITS / kClaim askers get kClaim units each.  The add for chunk c is issued before the
-        // wave reports chunk c - 1 as done, and LDS operations of a wave execute in order: once
-        // every wave is done with c - 1, all adds for c have been applied, so a fast wave's add
-        // for c + 2 (same counter) cannot get in between.
-        constexpr unsigned kClaim = S::UNITS / 4;
-        auto help_stage = [&](int chunk, bool report_done) {
-            const int p = chunk & 1;
-            unsigned got = 0;
-            if (fresh_lane() == 0) {
-                got = __hip_atomic_fetch_add(&tickets[p], kClaim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                if (report_done)                                       // chunk - 1 used the other buffer
-                    __hip_atomic_fetch_add(&done[p ^ 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
-            const unsigned unit0 = __builtin_amdgcn_readfirstlane(got) - unsigned(chunk >> 1) * (NW * kClaim);
-            if (unit0 < unsigned(S::UNITS)) {
-                wait_ge(&done[p], unsigned(chunk >> 1) * NW);          // chunk - 2 is finished: the buffer is free
-                for (unsigned u = 0; u < kClaim; ++u) stage_direct(chunk * CH, lds + p * BUF_FLOATS, int(unit0 + u));
-                __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0): the data is in LDS
-                if (fresh_lane() == 0)
-                    __hip_atomic_fetch_add(&staged[p], kClaim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
+                    : [recm] "v"(rec_m), [va] "v"(lds_base + buf_bytes + uint32_t(fresh_lane()) * 16u),
+                      [wa] "s"(wa), [first] "s"(0u), [cnt] "s"(nb), [chbfe] "n"(CH == 8 ? 0x30008 : 0x20008)
+                    : "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
+                      "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45",
+                      "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57",
+                      "v58", "v59", "v60", "v61", "v62", "v63",
+                      "s84", "s85", "s90", "s91", "s92", "s93", "s94", "s95", "scc");
+                // No "memory" clobber on purpose: it would make the compiler wait for the
+                // global->LDS loads of the next chunk, which may be in flight here and go to the
+                // other buffer.  What the loop reads was published before (barrier / counters), or
+                // written by the volatile stores in the batch path.
             }
         };
 
-        {
-            float4 rec_w;
-            fetch_records(0, k0, k_cnt, rec_m, rec_w);
-            if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
-        }
-        help_stage(0, false);
-        for (int chunk = 0; chunk < n_chunks; ++chunk) {
-            const bool more = chunk + 1 < n_chunks;
-            uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
-            float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (more) fetch_records(chunk + 1, nk0, nk_cnt, nrec_m, nrec_w);   // lands during the records below
-            wait_ge(&staged[chunk & 1], unsigned((chunk >> 1) + 1) * S::UNITS);
-            compute(chunk, k0, k_cnt, rec_m);
-            // every LDS read of this chunk has returned (the record loop waits for its loads)
-            if (more) {
-                if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
-                k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
-                help_stage(chunk + 1, true);
+        uint32_t k0, k_cnt, rec_m;
+        const int n_rel = c_end - c_begin;
+
+        if constexpr (VEC) {
+            // ---- no barrier in this loop: three counters per LDS buffer order the waves ----
+            //   tickets  staging work asked for           (a chunk has UNITS units of half a channel)
+            //   staged   staging units whose data landed  chunk r is readable when staged == UNITS * (r/2 + 1)
+            //   done     waves that finished a chunk      chunk r's buffer may be refilled (with chunk
+            //                                             r + 2) when done == NW * (r/2 + 1)
+            // All counters only grow.  A wave that has finished chunk r stages what is left of chunk
+            // r + 1 (once every wave is done with chunk r - 1, whose buffer it takes), then computes it:
+            // waves may be one chunk apart, so a chunk costs a wave its own records, not the records of
+            // the busiest wave, and the staging falls to the waves with the least to do.  The slowest
+            // wave never waits for a faster one: whatever it needs has been, or can be, produced by
+            // itself.  Waits are bounded (kSpinLimit) so that a mistake here ends in wrong results, not
+            // in a hang.
+            unsigned *tickets = sync_words, *staged = sync_words + 2, *done = sync_words + 4;
+            constexpr int kSpinLimit = 1 << 22;
+            auto wait_ge = [&](unsigned *p, unsigned target) {
+                for (int guard = 0; guard < kSpinLimit; ++guard) {
+                    const unsigned v = __builtin_amdgcn_readfirstlane(
+                        __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+                    if (v >= target) break;
+                    __builtin_amdgcn_s_sleep(2);
+                }
+            };
+            // A wave asks for staging work once per chunk, with one atomic add of kClaim: the counter
+            // of a buffer therefore advances by exactly NW * kClaim per chunk, and the first
+            // UNITS / kClaim askers get kClaim units each.  The add for chunk r is issued before the
+            // wave reports chunk r - 1 as done, and LDS operations of a wave execute in order: once
+            // every wave is done with r - 1, all adds for r have been applied, so a fast wave's add
+            // for r + 2 (same counter) cannot get in between.
+            constexpr unsigned kClaim = S::UNITS / 4;
+            auto help_stage = [&](int rel, bool report_done) {
+                const int p = rel & 1;
+                unsigned got = 0;
+                if (fresh_lane() == 0) {
+                    got = __hip_atomic_fetch_add(&tickets[p], kClaim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if (report_done)                                   // chunk rel - 1 used the other buffer
+                        __hip_atomic_fetch_add(&done[p ^ 1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+                const unsigned unit0 = __builtin_amdgcn_readfirstlane(got) - unsigned(rel >> 1) * (NW * kClaim);
+                if (unit0 < unsigned(S::UNITS)) {
+                    wait_ge(&done[p], unsigned(rel >> 1) * NW);        // chunk rel - 2 is finished: the buffer is free
+                    for (unsigned u = 0; u < kClaim; ++u)
+                        stage_direct((c_begin + rel) * CH, lds + p * BUF_FLOATS, int(unit0 + u));
+                    __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the data is in LDS
+                    if (fresh_lane() == 0)
+                        __hip_atomic_fetch_add(&staged[p], kClaim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                }
+            };
+
+            {
+                float4 rec_w;
+                fetch_records(c_begin, k0, k_cnt, rec_m, rec_w);
+                if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
+            }
+            help_stage(0, false);
+            for (int rel = 0; rel < n_rel; ++rel) {
+                const bool more = rel + 1 < n_rel;
+                uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
+                float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (more) fetch_records(c_begin + rel + 1, nk0, nk_cnt, nrec_m, nrec_w);   // lands during the records below
+                wait_ge(&staged[rel & 1], unsigned((rel >> 1) + 1) * S::UNITS);
+                compute(rel, k0, k_cnt, rec_m);
+                // every LDS read of this chunk has returned (the record loop waits for its loads)
+                if (more) {
+                    if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
+                    k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
+                    help_stage(rel + 1, true);
+                }
+            }
+        } else {
+            // ---- register staging path: fixed assignment, one barrier per chunk ----
+            {
+                float4 rec_w;
+                stage(0);
+                fetch_records(c_begin, k0, k_cnt, rec_m, rec_w);
+                if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
+                __syncthreads();
+            }
+            for (int rel = 0; rel < n_rel; ++rel) {
+                // The next chunk goes to the other LDS buffer, which every wave has finished reading
+                // (they all passed the barrier at the end of the previous iteration).
+                const bool more = rel + 1 < n_rel;
+                uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
+                float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (more) {
+                    stage(rel + 1);
+                    fetch_records(c_begin + rel + 1, nk0, nk_cnt, nrec_m, nrec_w);
+                }
+                compute(rel, k0, k_cnt, rec_m);
+                if (more) {
+                    if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
+                    k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
+                    __syncthreads();
+                }
             }
         }
-        __syncthreads();
-    } else {
-        // ---- register staging path: fixed assignment, one barrier per chunk ----
-        {
-            float4 rec_w;
-            stage(0);
-            fetch_records(0, k0, k_cnt, rec_m, rec_w);
-            if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
-            __syncthreads();
-        }
-        for (int chunk = 0; chunk < n_chunks; ++chunk) {
-            // The next chunk goes to the other LDS buffer, which every wave has finished reading
-            // (they all passed the barrier at the end of the previous iteration).
-            const bool more = chunk + 1 < n_chunks;
-            uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
-            float4 nrec_w = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (more) {
-                stage(chunk + 1);
-                fetch_records(chunk + 1, nk0, nk_cnt, nrec_m, nrec_w);
-            }
-            compute(chunk, k0, k_cnt, rec_m);
-            if (more) {
-                if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
-                k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
+
+        // ---- channel splits: add the partial sums through LDS, split 2s+1 into 2s, then 2 into 0 ----
+        if (ks_log2 > 0) {
+            __syncthreads();                             // the staging buffers are free now
+            float4 *red = reinterpret_cast<float4 *>(lds);
+            for (int step = (1 << ks_log2) >> 1; step >= 1; step >>= 1) {
+                const bool sender = ksplit >= step && ksplit < 2 * step;
+                const bool receiver = ksplit < step;
+                // slot of (filter block fbw, split): 16 float4 per lane
+                const int fbw = wave - ksplit * fw;
+                const int slot = ((sender ? ksplit - step : ksplit) * fw + fbw) * (16 * 64);
+                if (sender) {
+#pragma unroll
+                    for (int s = 0; s < FB; ++s)
+#pragma unroll
+                        for (int qd = 0; qd < 4; ++qd)
+                            red[slot + (s * 4 + qd) * 64 + lane] =
+                                make_float4(acc[s][4 * qd], acc[s][4 * qd + 1], acc[s][4 * qd + 2], acc[s][4 * qd + 3]);
+                }
+                __syncthreads();
+                if (receiver) {
+#pragma unroll
+                    for (int s = 0; s < FB; ++s)
+#pragma unroll
+                        for (int qd = 0; qd < 4; ++qd) {
+                            const float4 p = red[slot + (s * 4 + qd) * 64 + lane];
+                            acc[s][4 * qd] += p.x; acc[s][4 * qd + 1] += p.y; acc[s][4 * qd + 2] += p.z; acc[s][4 * qd + 3] += p.w;
+                        }
+                }
                 __syncthreads();
             }
         }
-    }
 
-    // ---- channel splits: add the partial sums through LDS, split 2s+1 into 2s, then 2 into 0 ----
-    if (ks_log2 > 0) {
-        __syncthreads();                                 // the staging buffers are free now
-        float4 *red = reinterpret_cast<float4 *>(lds);
-        for (int step = (1 << ks_log2) >> 1; step >= 1; step >>= 1) {
-            const bool sender = ksplit >= step && ksplit < 2 * step;
-            const bool receiver = ksplit < step;
-            // slot of (filter block fbw, split): 16 float4 per lane
-            const int fbw = wave - ksplit * fw;
-            const int slot = ((sender ? ksplit - step : ksplit) * fw + fbw) * (16 * 64);
-            if (sender) {
-#pragma unroll
-                for (int s = 0; s < FB; ++s)
-#pragma unroll
-                    for (int qd = 0; qd < 4; ++qd)
-                        red[slot + (s * 4 + qd) * 64 + lane] =
-                            make_float4(acc[s][4 * qd], acc[s][4 * qd + 1], acc[s][4 * qd + 2], acc[s][4 * qd + 3]);
-            }
-            __syncthreads();
-            if (receiver) {
-#pragma unroll
-                for (int s = 0; s < FB; ++s)
-#pragma unroll
-                    for (int qd = 0; qd < 4; ++qd) {
-                        const float4 p = red[slot + (s * 4 + qd) * 64 + lane];
-                        acc[s][4 * qd] += p.x; acc[s][4 * qd + 1] += p.y; acc[s][4 * qd + 2] += p.z; acc[s][4 * qd + 3] += p.w;
+        // ---- epilogue ----
+        // Whole unit, or its last chunks: bias, ReLU, store (filters go back to their original
+        // index).  A piece that takes over first adds what the previous workgroup left in the
+        // output tensor; a piece that hands on stores the raw sums there instead.
+        // the patch coordinates are recomputed here instead of being kept in registers across the loop
+        int pidx_e = tile * 64 + lane;
+        asm volatile("" : "+v"(pidx_e));
+        const bool writer = active && ksplit == 0 && pidx_e < a.n_patches;
+        if constexpr (VEC && SPLIT) {
+            if (takes_over) {
+                // The predecessor (id - 8: same set, previous range) started before this workgroup
+                // and ran the shared unit first, so this wait is normally over before it begins.
+                // It is bounded all the same; if it ever expires the outputs are poisoned with NaN.
+                // One wave polls, and only its successful read is followed by the (costly)
+                // device-wide acquire; the barrier passes it on to the other waves.
+                if (wave == 0) {
+                    bool there = false;
+                    for (int guard = 0; guard < (1 << 20) && !there; ++guard) {
+                        there = __hip_atomic_load(a.flags + (blockIdx.x - 8), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
+                        if (!there) __builtin_amdgcn_s_sleep(8);
                     }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                    if (!there && lane == 0) sync_words[6] = 1u;
+                }
+                __syncthreads();
+                if (sync_words[6]) {
+#pragma unroll
+                    for (int s = 0; s < FB; ++s) acc[s] = __builtin_nanf("");
+                }
             }
-            __syncthreads();
         }
-    }
-
-    // ---- epilogue: bias, ReLU, store (filters go back to their original index) ----
-    if (!active || ksplit != 0) return;
-    // the patch coordinates are recomputed here instead of being kept in registers across the loop
-    int pidx_e = tile * 64 + lane;
-    asm volatile("" : "+v"(pidx_e));
-    if (pidx_e >= a.n_patches) return;
-    const int n_e = pidx_e / per_img, prem_e = pidx_e - n_e * per_img;
-    const int ye = (prem_e / a.px) * 4;
-    const int xe = VEC ? min((prem_e % a.px) * 4, a.w - 4) : (prem_e % a.px) * 4;
-    const int ho = a.h, wo = a.w;
+        if (writer) {
+            const int n_e = pidx_e / per_img, prem_e = pidx_e - n_e * per_img;
+            const int ye = (prem_e / a.px) * 4;
+            const int xe = VEC ? min((prem_e % a.px) * 4, a.w - 4) : (prem_e % a.px) * 4;
+            const int ho = a.h, wo = a.w;
 #pragma unroll
-    for (int s = 0; s < FB; ++s) {
-        const int f = a.slot_filter[fblk * FB + s];
-        if (f < 0) continue;
-        const float b = a.bias ? a.bias[f] : 0.0f;
+            for (int s = 0; s < FB; ++s) {
+                const int f = a.slot_filter[fblk * FB + s];
+                if (f < 0) continue;
+                const float b = (a.bias && !hands_on) ? a.bias[f] : 0.0f;
+                if constexpr (VEC) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int oy = ye + i;
-            if (oy >= ho) continue;
-            float o[4];
+                    for (int i = 0; i < 4; ++i) {
+                        if (ye + i >= ho) continue;
+                        float *dst = reinterpret_cast<float *>(y) + ((size_t(n_e) * a.c_out + f) * ho + ye + i) * wo + xe;
+                        float o[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                o[k] = acc[s][i * 4 + k] + b;
-                if (a.relu) o[k] = fmaxf(o[k], 0.0f);
+                        for (int k = 0; k < 4; ++k) o[k] = acc[s][i * 4 + k];
+                        if (takes_over) {
+                            const float4 p = *reinterpret_cast<const float4 *>(dst);
+                            o[0] += p.x; o[1] += p.y; o[2] += p.z; o[3] += p.w;
+                        }
+                        if (!hands_on) {
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) { o[k] += b; if (a.relu) o[k] = fmaxf(o[k], 0.0f); }
+                        }
+                        *reinterpret_cast<float4 *>(dst) = make_float4(o[0], o[1], o[2], o[3]);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int oy = ye + i;
+                        if (oy >= ho) continue;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            float v = acc[s][i * 4 + k] + b;
+                            if (a.relu) v = fmaxf(v, 0.0f);
+                            if (xe + k < wo) st_act(y, act_at<T, LAYOUT>(n_e, f, oy, xe + k, a.c_out, ho, wo), v);
+                        }
+                    }
+                }
             }
-            if (VEC) {
-                float *dst = reinterpret_cast<float *>(y) + ((size_t(n_e) * a.c_out + f) * ho + oy) * wo + xe;
-                *reinterpret_cast<float4 *>(dst) = make_float4(o[0], o[1], o[2], o[3]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (xe + k < wo) st_act(y, act_at<T, LAYOUT>(n_e, f, oy, xe + k, a.c_out, ho, wo), o[k]);
+        }
+        if constexpr (VEC && SPLIT) {
+            if (hands_on) {
+                // the barrier orders every thread's stores before the release below, which makes
+                // them visible to the whole device before the successor is told
+                __syncthreads();
+                if (threadIdx.x == 0)
+                    __hip_atomic_store(a.flags + blockIdx.x, a.epoch, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }
 }
 
-template <typename T, int LAYOUT, bool VEC, int NW, int CH>
+template <typename T, int LAYOUT, bool VEC, int NW, int CH, bool SPLIT>
 hipError_t launch_shape(const TiledArgs &a, int64_t wgs, hipStream_t st)
 {
     static bool attr_done = false;       // (set to the same value by every thread that gets here first)
     constexpr size_t lds_bytes = Shape<NW, CH>::LDS_BYTES;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_tiled_kernel<T, LAYOUT, VEC, NW, CH>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_tiled_kernel<T, LAYOUT, VEC, NW, CH, SPLIT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL((conv_tiled_kernel<T, LAYOUT, VEC, NW, CH>), dim3(unsigned(wgs)), dim3(NW * 64), lds_bytes, st, a);
+    hipLaunchKernelGGL((conv_tiled_kernel<T, LAYOUT, VEC, NW, CH, SPLIT>), dim3(unsigned(wgs)), dim3(NW * 64), lds_bytes, st, a);
     return hipGetLastError();
 }
 
 template <int NW, int CH>
 hipError_t launch_any(const TiledArgs &a, int64_t wgs, hipStream_t st, bool vec, int layout, int dtype)
 {
-    if (vec) return launch_shape<float, PCONV_NCHW, true, NW, CH>(a, wgs, st);
+    if (vec)
+        return a.split_units ? launch_shape<float, PCONV_NCHW, true, NW, CH, true>(a, wgs, st)
+                             : launch_shape<float, PCONV_NCHW, true, NW, CH, false>(a, wgs, st);
     if (dtype == PCONV_F32)
-        return layout == PCONV_NCHW ? launch_shape<float, PCONV_NCHW, false, NW, CH>(a, wgs, st)
-                                    : launch_shape<float, PCONV_NHWC, false, NW, CH>(a, wgs, st);
-    return layout == PCONV_NCHW ? launch_shape<bf16_t, PCONV_NCHW, false, NW, CH>(a, wgs, st)
-                                : launch_shape<bf16_t, PCONV_NHWC, false, NW, CH>(a, wgs, st);
+        return layout == PCONV_NCHW ? launch_shape<float, PCONV_NCHW, false, NW, CH, false>(a, wgs, st)
+                                    : launch_shape<float, PCONV_NHWC, false, NW, CH, false>(a, wgs, st);
+    return layout == PCONV_NCHW ? launch_shape<bf16_t, PCONV_NCHW, false, NW, CH, false>(a, wgs, st)
+                                : launch_shape<bf16_t, PCONV_NHWC, false, NW, CH, false>(a, wgs, st);
 }
 
-int g_force_waves = 0, g_force_ks = -1;    // test overrides, see set_tiled_tuning
+int g_force_waves = 0, g_force_ks = -1, g_force_split = -1;    // test overrides, see set_tiled_tuning
 
 }  // namespace
 
-void set_tiled_tuning(int waves, int ks_log2)
+void set_tiled_tuning(int waves, int ks_log2, int split_units)
 {
     g_force_waves = (waves == 8 || waves == 16) ? waves : 0;
     g_force_ks = (ks_log2 >= 0 && ks_log2 <= 2) ? ks_log2 : -1;
+    g_force_split = (split_units == 0 || split_units == 1) ? split_units : -1;
 }
 
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype)
@@ -565,18 +668,43 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     a.n_blocks = h->tiled.num_blocks;
     a.relu = relu;
     const bool vec = dtype == PCONV_F32 && layout == PCONV_NCHW && win >= 4;
-    const int64_t tiles8 = int64_t((a.n_tiles + 7) / 8) * 8;
-    // Shape: 16-wave workgroups, one per compute unit, unless the test override asks otherwise.
-    const int nw = g_force_waves ? g_force_waves : 16;
-    // channel split: as long as the workgroups would not even fill the 256 compute units once
+    // Shape: 16-wave workgroups, one per compute unit.  A layer whose input channels fit one 4-channel
+    // chunk is all staging and output stores: there two 8-wave workgroups per compute unit overlap
+    // one's stores with the other's loads.
+    const int nw = g_force_waves ? g_force_waves : (h->c_in <= 4 ? 8 : 16);
+    const int ch = nw == 16 ? 8 : 4;
+    a.n_chunks = (h->c_in + ch - 1) / ch;
+    // Few units: share them between workgroups (needs fp32 outputs written 128 bits at a time, the
+    // VEC kernel), else split the channels inside the workgroups.
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device) != hipSuccess || cus <= 0) cus = 256;
+    const int slots = cus * (16 / nw);                   // workgroups that can run at once
+    // Sharing units costs every workgroup a second start-up and a pass of the partial sums through
+    // memory: it pays where whole units would leave half of the compute units or more without work.
+    a.split_units = vec && int64_t(a.n_tiles) * ((a.n_blocks + nw - 1) / nw) <= slots / 2;
+    if (g_force_split >= 0) a.split_units = vec ? g_force_split : 0;
     a.ks_log2 = 0;
-    while (a.ks_log2 < 2 && tiles8 * ((a.n_blocks + (nw >> a.ks_log2) - 1) / (nw >> a.ks_log2)) <= 128 * (16 / nw))
-        ++a.ks_log2;
+    if (!a.split_units)
+        while (a.ks_log2 < 2 && int64_t(a.n_tiles) * ((a.n_blocks + (nw >> a.ks_log2) - 1) / (nw >> a.ks_log2)) <= slots / 2)
+            ++a.ks_log2;
     if (g_force_ks >= 0) a.ks_log2 = g_force_ks;
     const int fw = nw >> a.ks_log2;
     a.n_groups = (a.n_blocks + fw - 1) / fw;
-    const int64_t wgs = tiles8 * a.n_groups;
-    if (wgs > 0x7FFFFFFF) { set_error("pconv_conv2d: too many workgroups"); return PCONV_UNSUPPORTED; }
+    const int64_t units = int64_t(a.n_tiles) * a.n_groups;
+    if (units > 0x3FFFFFFF) { set_error("pconv_conv2d: too many workgroups"); return PCONV_UNSUPPORTED; }
+    a.n_units = int(units);
+    int64_t wgs;
+    a.flags = nullptr; a.epoch = 0;
+    if (a.split_units) {
+        // one workgroup per slot, but no fewer than two chunks each
+        const int64_t iters = units * a.n_chunks;
+        wgs = std::min<int64_t>(std::min<int>(slots, kFlagWords), std::max<int64_t>(8, iters / 2));
+        const uint32_t call = h->calls.fetch_add(1u);
+        a.flags = h->d_flags + size_t(call % kFlagSlots) * kFlagWords;
+        a.epoch = call + 1u ? call + 1u : 1u;
+    } else {
+        wgs = int64_t((a.n_tiles + 7) / 8) * 8 * a.n_groups;   // one per unit of the largest set, in every set
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const hipError_t e = nw == 16 ? launch_any<16, 8>(a, wgs, st, vec, layout, dtype)
                                   : launch_any<8, 4>(a, wgs, st, vec, layout, dtype);

@@ -22,7 +22,7 @@ POLICIES = [1, 0]          # 1 = generic gather kernel, 0 = automatic (register-
 def _reset_policy():
     yield
     P.pconv_set_kernel_policy(0)
-    P.pconv_debug_set_tiling(0, -1)
+    P.pconv_debug_set_tiling(0, -1, -1)
 
 
 def check_full(spec, L, x, dtype, layout="nchw", stride=1, relu=False, use_bias=True, policy=0, what=""):
@@ -162,19 +162,21 @@ TILING_SHAPES = [  # (n, c_in, c_out, h, w): several chunks and filter groups, r
 ]
 
 
+@pytest.mark.parametrize("split_units", [0, 1])
 @pytest.mark.parametrize("ks_log2", [0, 1, 2])
 @pytest.mark.parametrize("waves", [8, 16])
-def test_tiled_kernel_every_workgroup_shape_and_channel_split(waves, ks_log2):
-    """The register-tiled kernel in both workgroup shapes and all three channel splits, which the
-    automatic choice only picks for particular layer sizes."""
-    P.pconv_debug_set_tiling(waves, ks_log2)
+def test_tiled_kernel_every_workgroup_shape_and_channel_split(waves, ks_log2, split_units):
+    """The register-tiled kernel in both workgroup shapes, all three channel splits inside a
+    workgroup, with and without units shared between workgroups: choices the automatic
+    selection only makes for particular layer sizes."""
+    P.pconv_debug_set_tiling(waves, ks_log2, split_units)
     for j, (n, ci, co, h, w) in enumerate(TILING_SHAPES):
         for dtype, layout in (("f32", "nchw"), ("bf16", "nhwc")):
             spec = LayerSpec(f"tiling{j}", n, ci, co, h, w, dtype=dtype, num_patterns=12,
                              pattern_dist="uniform", keep_div=2.0, count_dist="bernoulli")
             L = make_layer(spec, 2000 + j); x = make_input(spec, 2000 + j, layout)
             check_full(spec, L, x, dtype, layout, 1, relu=bool(j & 1), policy=2,
-                       what=f"tiling{j}_w{waves}_ks{ks_log2}")
+                       what=f"tiling{j}_w{waves}_ks{ks_log2}_split{split_units}")
 
 
 @pytest.mark.parametrize("policy", POLICIES)
