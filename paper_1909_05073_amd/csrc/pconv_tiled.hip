@@ -55,7 +55,7 @@ template <int NW, int CH> struct Shape {
     static constexpr size_t LDS_BYTES = size_t(OFF_HALO + HALO_TAB_WORDS) * 4;
     static constexpr int UNITS = 2 * CH;                       // staging units of half a channel per chunk
     static constexpr int SEGS = CH * 6 / NW;                   // (channel, row) segments per wave (register path)
-    static_assert(CH * 6 % NW == 0 && UNITS % 4 == 0 && CH <= kTileCH && kTileCH % CH == 0, "unsupported shape");
+    static_assert(CH * 6 % NW == 0 && UNITS % 8 == 0 && CH <= kTileCH && kTileCH % CH == 0, "unsupported shape");
 };
 
 static_assert(kNumCodes == 24 && FB == 4 && BATCH == 32 && kTileCH == 8,
@@ -247,28 +247,29 @@ conv_tiled_kernel(const TiledArgs a)
             const bool cv = c0 + ch < a.c_in;
             const float *xc = reinterpret_cast<const float *>(x) + (c0 + ch) * hw;
             float *cbuf = buf + ch * CHAN_FLOATS;
+            // everything the lane needs from the tables first, so that there is one wait for LDS
+            const int lane_off_now = inv[2 * ln];
+            const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
+            int off[6];
+#pragma unroll
+            for (int k = 0; k < 6; ++k) off[k] = halo_tab[(6 * half + k) * 64 + ln];
             // The LDS address of lane 0's element goes to M0 and every lane adds lane * size.  Written
             // as assembly so that the compiler does not track these loads: it would otherwise wait for
             // them before the record loop (they are waited for explicitly before they are published).
-            {
-                const int lane_off_now = inv[2 * ln];
-                const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
 #pragma unroll
-                for (int k = 0; k < 3; ++k) {
-                    const int r = 3 * half + k;
-                    const float *src = xc + (lane_off_now + r * a.w);
-                    const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + r * QUAD_FLOATS));
-                    if (cv && ((vmask >> r) & 1u))
-                        asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst_b));
-                }
+            for (int k = 0; k < 3; ++k) {
+                const int r = 3 * half + k;
+                const float *src = xc + (lane_off_now + r * a.w);
+                const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + r * QUAD_FLOATS));
+                if (cv && ((vmask >> r) & 1u))
+                    asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst_b));
             }
 #pragma unroll
             for (int k = 0; k < 6; ++k) {
                 const int j = 6 * half + k;
-                const int off = halo_tab[j * 64 + ln];
-                const float *src = xc + off;
+                const float *src = xc + off[k];
                 const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + 6 * QUAD_FLOATS + j * 64));
-                if (cv && off >= 0)
+                if (cv && off[k] >= 0)
                     asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dword %0, off" ::"v"(src), "s"(dst_b));
             }
         };
@@ -416,11 +417,11 @@ conv_tiled_kernel(const TiledArgs a)
             };
             // A wave asks for staging work once per chunk, with one atomic add of kClaim: the counter
             // of a buffer therefore advances by exactly NW * kClaim per chunk, and the first
-            // UNITS / kClaim askers get kClaim units each.  The add for chunk r is issued before the
+            // UNITS / kClaim askers (eight) get kClaim units each.  The add for chunk r is issued before the
             // wave reports chunk r - 1 as done, and LDS operations of a wave execute in order: once
             // every wave is done with r - 1, all adds for r have been applied, so a fast wave's add
             // for r + 2 (same counter) cannot get in between.
-            constexpr unsigned kClaim = S::UNITS / 4;
+            constexpr unsigned kClaim = S::UNITS / 8;
             auto help_stage = [&](int rel, bool report_done) {
                 const int p = rel & 1;
                 unsigned got = 0;
