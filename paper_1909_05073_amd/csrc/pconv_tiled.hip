@@ -184,6 +184,17 @@ conv_tiled_kernel(const TiledArgs a)
 
         if (SPLIT) __syncthreads();                      // every wave has left the previous piece: LDS is free
 
+        // The records of a (filter block, chunk) are contiguous and ordered by channel, so this wave's
+        // share of a chunk is the range between two entries of chan_ptr.  The range bounds of up to
+        // 64 consecutive chunks sit one per lane in ptr_lo / ptr_hi and are read with v_readlane.
+        // (Loaded first: they are on the way while the tables below are set up.)
+        const int ptr_max = a.row_len - 1;               // last entry of a row: end of the block's records
+        const uint32_t *__restrict__ ptr_row = a.chan_ptr + size_t(active ? fblk : 0) * a.row_len;
+        int win_base = c_begin;
+        uint32_t ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, ptr_max)];
+        uint32_t ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, ptr_max)];
+
+
         // this lane's patch
         const int pidx = tile * 64 + lane;
         const bool pvalid = pidx < a.n_patches;
@@ -327,15 +338,6 @@ conv_tiled_kernel(const TiledArgs a)
         }
         __syncthreads();                                 // zeroed buffers, tables and counters are visible
 
-        // The records of a (filter block, chunk) are contiguous and ordered by channel, so this wave's
-        // share of a chunk is the range between two entries of chan_ptr.  The range bounds of up to
-        // 64 consecutive chunks sit one per lane in ptr_lo / ptr_hi and are read with v_readlane.
-        const int ptr_max = a.row_len - 1;               // last entry of a row: end of the block's records
-        const uint32_t *__restrict__ ptr_row = a.chan_ptr + size_t(active ? fblk : 0) * a.row_len;
-        int win_base = c_begin;
-        uint32_t ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, ptr_max)];
-        uint32_t ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, ptr_max)];
-
         // record range of this wave for a chunk, and the fetch of its first batch: lane j gets record
         // j (k0 + k_cnt is the next record or the padding record, always readable)
         auto fetch_records = [&](int chunk, uint32_t &k0, uint32_t &k_cnt, uint32_t &rec_m, float4 &rec_w) {
@@ -443,10 +445,10 @@ conv_tiled_kernel(const TiledArgs a)
 
             {
                 float4 rec_w;
-                fetch_records(c_begin, k0, k_cnt, rec_m, rec_w);
+                fetch_records(c_begin, k0, k_cnt, rec_m, rec_w);       // on the way while chunk 0 is staged
+                help_stage(0, false);
                 if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = rec_w;
             }
-            help_stage(0, false);
             for (int rel = 0; rel < n_rel; ++rel) {
                 const bool more = rel + 1 < n_rel;
                 uint32_t nk0 = 0, nk_cnt = 0, nrec_m = 0;
