@@ -22,10 +22,7 @@ quad per lane: the six rows, then the twelve halo values), %[wa] LDS byte addres
 of this wave's weight block (SGPR; 16 bytes per record), %[first] %[cnt] the records to run
 (SGPRs; first <= cnt <= 32; nothing is done when they are equal).
 """
-import os
 import sys
-
-EXP = os.environ.get('PCONV_GEN_EXP', '')   # timing experiments only
 
 ACC, INP, WREG = 64, 28, 24
 STRIDE_LOG2 = 9
@@ -47,20 +44,11 @@ def fetch(lines):
         "s_nop 0",
         "s_bitcmp1_b32 s85, 11",
     ]
-    if 'nopatch' not in EXP:
-        lines.append("s_cbranch_scc1 PATCH_%=")
-    if 'noweights' in EXP:
-        lines.remove("ds_read_b128 v[%d:%d], v23" % (WREG, WREG + 3))
+    lines.append("s_cbranch_scc1 PATCH_%=")
     jump(lines)
 
 
 def jump(lines):
-    if 'seq' in EXP:
-        return
-    if 'nojump' in EXP:
-        lines += ["s_and_b32 s90, s85, 0", "s_min_u32 s90, s90, 95", "s_lshl_b32 s90, s90, 9",
-                  "s_add_u32 s94, s92, s90", "s_addc_u32 s95, s93, 0", "s_branch TABLE_%="]
-        return
     lines += [
         "s_and_b32 s90, s85, 0xff",
         "s_min_u32 s90, s90, %d" % (SLOTS * len(CODE_MASKS) - 1),
@@ -90,10 +78,11 @@ def generate():
         "s_add_u32 s92, s92, TABLE_%=-BASE_%=",
         "s_addc_u32 s93, s93, 0",
         "s_mov_b32 s84, %[first]",
+        # The records run at the lowest issue priority, everything around them (staging the next
+        # chunk, the counters that other waves wait for) at the highest: see DONE below.
+        "s_setprio 0",
     ]
     fetch(L)
-    if 'seq' in EXP:
-        L.append("s_branch TABLE_%=")
     # out of line: a new channel starts, reload the lane's 6x6 neighbourhood from LDS
     L += [
         "PATCH_%=:",
@@ -109,8 +98,6 @@ def generate():
     L.append("TABLE_%=:")
     for slot in range(SLOTS):
         for mask in CODE_MASKS:
-            if 'same' in EXP:
-                mask = 0x03A
             L.append("s_waitcnt lgkmcnt(0)")
             j = 0
             for t in range(9):
@@ -128,11 +115,9 @@ def generate():
                 "s_cbranch_scc1 DONE_%=",
             ]
             fetch(L)
-            if 'seq' not in EXP:
-                L.append(".p2align %d" % STRIDE_LOG2)
-    if 'seq' in EXP:
-        L.append("s_branch TABLE_%=")
+            L.append(".p2align %d" % STRIDE_LOG2)
     L.append("DONE_%=:")
+    L.append("s_setprio 3")
     return L
 
 

@@ -120,6 +120,9 @@ conv_tiled_kernel(const TiledArgs a)
     using S = Shape<NW, CH>;
     constexpr int BUF_FLOATS = S::BUF_FLOATS;
     extern __shared__ __attribute__((aligned(16))) float lds[];
+    // Everything outside the record loop (staging, the counters other waves wait for, the
+    // epilogue) runs at the highest issue priority; the record loop drops to the lowest.
+    __builtin_amdgcn_s_setprio(3);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
