@@ -122,7 +122,8 @@ int build_canonical(const float *w, const uint8_t *pid, const uint8_t *conn, con
 // runs the kernels of its kTileFB filters one after another, so what must be equal across
 // waves is the SUM of their kernel counts: the filters, already sorted by kernel count, are
 // dealt to the blocks in serpentine order (0..NB-1, NB-1..0, ...), which gives every block
-// one filter from each slice of the sorted list.
+// one filter from each slice of the sorted list; a local search then evens the counts out
+// chunk by chunk (see below).
 void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int c_out, int c_in,
                         TiledStream &out)
 {
@@ -157,6 +158,62 @@ void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int 
                     pc.tap_rank[pc.ntaps++] = __builtin_popcount(unsigned(table[p]) & ((1u << t) - 1u));
             pieces[p].push_back(pc);
             left &= ~unsigned(kCodeMask[best]);
+        }
+    }
+
+    // Second step of the balance: the waves of a workgroup walk the input channels chunk by chunk
+    // (kTileCH channels) and may drift at most a chunk apart, so their record counts should agree
+    // chunk by chunk, not only in total.  Within every group of kTileWaves blocks (the filters of
+    // one workgroup) filters are swapped between blocks while that lowers
+    //     sum over blocks b [ sum over chunks j of L(b, j)^2  +  (sum over chunks j of L(b, j))^2 / J ],
+    // L(b, j) = records of block b in chunk j: a plain local search, deterministic, a few passes.
+    {
+        const int J = cpad / kTileCH;
+        const int GW = kTileWaves;
+        std::vector<int> cnt;                                 // [slots of the group][J] records of the slot's filter
+        std::vector<int64_t> load, total;
+        for (int g0 = 0; g0 < nb; g0 += GW) {
+            const int gb = std::min(GW, nb - g0), gs = gb * FB;
+            cnt.assign(size_t(gs) * J, 0);
+            for (int sl = 0; sl < gs; ++sl) {
+                const int pos = slot_pos[size_t(g0) * FB + sl];
+                if (pos < 0) continue;
+                for (uint32_t k = cn.row_ptr[pos]; k < cn.row_ptr[pos + 1]; ++k)
+                    cnt[size_t(sl) * J + cn.cin[k] / kTileCH] += int(pieces[cn.pat[k]].size());
+            }
+            load.assign(size_t(gb) * J, 0); total.assign(gb, 0);
+            for (int sl = 0; sl < gs; ++sl)
+                for (int j = 0; j < J; ++j) { load[size_t(sl / FB) * J + j] += cnt[size_t(sl) * J + j]; total[sl / FB] += cnt[size_t(sl) * J + j]; }
+            for (int pass = 0; pass < 16; ++pass) {
+                bool improved = false;
+                for (int sa = 0; sa < gs; ++sa)
+                    for (int sb = sa + 1; sb < gs; ++sb) {
+                        const int ba = sa / FB, bb = sb / FB;
+                        if (ba == bb) continue;
+                        // cost change if the filters in slots sa and sb trade places (times J, to stay in integers)
+                        int64_t delta = 0, ta = 0, tb = 0;
+                        for (int j = 0; j < J; ++j) {
+                            const int64_t d = int64_t(cnt[size_t(sb) * J + j]) - cnt[size_t(sa) * J + j];   // block a gains d, block b loses d
+                            const int64_t la = load[size_t(ba) * J + j], lb = load[size_t(bb) * J + j];
+                            delta += (la + d) * (la + d) - la * la + (lb - d) * (lb - d) - lb * lb;
+                            ta += d;
+                        }
+                        tb = -ta;
+                        delta = delta * J + (total[ba] + ta) * (total[ba] + ta) - total[ba] * total[ba]
+                                          + (total[bb] + tb) * (total[bb] + tb) - total[bb] * total[bb];
+                        if (delta >= 0) continue;
+                        for (int j = 0; j < J; ++j) {
+                            const int64_t d = int64_t(cnt[size_t(sb) * J + j]) - cnt[size_t(sa) * J + j];
+                            load[size_t(ba) * J + j] += d; load[size_t(bb) * J + j] -= d;
+                            std::swap(cnt[size_t(sa) * J + j], cnt[size_t(sb) * J + j]);
+                        }
+                        total[ba] += ta; total[bb] += tb;
+                        std::swap(out.slot_filter[size_t(g0) * FB + sa], out.slot_filter[size_t(g0) * FB + sb]);
+                        std::swap(slot_pos[size_t(g0) * FB + sa], slot_pos[size_t(g0) * FB + sb]);
+                        improved = true;
+                    }
+                if (!improved) break;
+            }
         }
     }
 
