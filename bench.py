@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--policy", type=int, default=0, help="kernel policy (0 auto, 1 generic, 2 tiled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fuse-pool", action="store_true",
+                    help="run every max-pool as a kernel of its own instead of in the epilogue of the convolution")
     ap.add_argument("--profile-copy-mb", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (calibrates rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters against a kernel of known traffic)")
@@ -60,11 +62,16 @@ def main():
         h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
         nnz = nnz_of_layer(L)
         flop = 2.0 * nnz * n * spec.h_out * spec.w_out
-        byts = 4.0 * (n * spec.c_in * spec.h * spec.w + n * spec.c_out * spec.h_out * spec.w_out) \
-            + 4.0 * nnz + 2.0 * int(L["conn"].sum())
+        # The max-pool after a layer goes into the convolution's epilogue, except where the layer has so
+        # few tiles that the library shares them between workgroups through the full-size output
+        # (conv13 at batch 32), which a fused pool would rule out.
+        units = -(-(n * -(-spec.h // 4) * -(-spec.w // 4)) // 64) * -(-spec.c_out // 64)
+        fuse = bool(spec.pool_after) and not args.no_fuse_pool and args.policy != 1 and units > 128
+        out_elems = n * spec.c_out * ((spec.h_out // 2) * (spec.w_out // 2) if fuse else spec.h_out * spec.w_out)
+        byts = 4.0 * (n * spec.c_in * spec.h * spec.w + out_elems) + 4.0 * nnz + 2.0 * int(L["conn"].sum())
         layers.append(dict(spec=spec, L=L, h=h, bias=torch.from_numpy(L["bias"]).to(dev), nnz=nnz,
-                           flop=flop, bytes=byts,
-                           y=torch.empty((n, spec.c_out, spec.h_out, spec.w_out), device=dev),
+                           flop=flop, bytes=byts, fuse=fuse,
+                           y=(None if fuse else torch.empty((n, spec.c_out, spec.h_out, spec.w_out), device=dev)),
                            p=(torch.empty((n, spec.c_out, spec.h_out // 2, spec.w_out // 2), device=dev)
                               if spec.pool_after else None)))
     g = torch.Generator(device=dev); g.manual_seed(base_seed(3))
@@ -77,6 +84,13 @@ def main():
             s = ly["spec"]
             if events is not None:
                 events[i][0].record()
+            if ly["fuse"]:
+                P.pconv_conv2d_pool2x2(ly["h"], cur.data_ptr(), ly["p"].data_ptr(), ly["bias"].data_ptr(), n, s.h, s.w,
+                                       P.NCHW, P.F32, True, stream)
+                if events is not None:
+                    events[i][1].record()
+                cur = ly["p"]
+                continue
             P.pconv_conv2d(ly["h"], cur.data_ptr(), ly["y"].data_ptr(), ly["bias"].data_ptr(), n, s.h, s.w,
                            1, 1, P.NCHW, P.F32, True, stream)
             if events is not None:
@@ -112,7 +126,7 @@ def main():
         ms = float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)]))
         conv_ms_total += ms
         t_roof_ms = max(ly["flop"] / (PEAK_VEC_TFLOPS * 1e12), ly["bytes"] / (PEAK_HBM_GBS * 1e9)) * 1e3
-        per_layer.append(dict(layer=ly["spec"].name, ms=round(ms, 4),
+        per_layer.append(dict(layer=ly["spec"].name + ("+pool" if ly["fuse"] else ""), ms=round(ms, 4),
                               eff_tflops=round(ly["flop"] / ms / 1e9, 2),
                               alg_gbs=round(ly["bytes"] / ms / 1e6, 1),
                               binds="hbm" if ly["bytes"] / (PEAK_HBM_GBS * 1e9) > ly["flop"] / (PEAK_VEC_TFLOPS * 1e12) else "alu",
@@ -127,12 +141,13 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"vgg16_3x3_stack_13conv_batch{n}_fp32_8pattern_conn3.6x",
-                   "global_batch": n, "layout": "nchw", "kernel_policy": args.policy},
+                   "global_batch": n, "layout": "nchw", "kernel_policy": args.policy,
+                   "fused_maxpools": sum(1 for ly in layers if ly["fuse"])},
         "roofline": {"bound": "alu", "achieved": round(achieved, 3), "peak": PEAK_VEC_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_VEC_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES_BATCH32 if (n == 32 and args.policy == 0) else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES_BATCH32 if (n == 32 and args.policy == 0 and not args.no_fuse_pool) else None,
                      "algorithmic_flop": total_flop, "algorithmic_bytes": sum(ly["bytes"] for ly in layers),
-                     "kernel": "pconv_conv2d (13 launches per step, summed)",
+                     "kernel": "pconv_conv2d / pconv_conv2d_pool2x2 (13 launches per step, summed)",
                      "conv_ms_per_step": round(conv_ms_total, 4),
                      "stack_roof_frac": round(sum(max(ly["flop"] / (PEAK_VEC_TFLOPS * 1e12),
                                                       ly["bytes"] / (PEAK_HBM_GBS * 1e9)) for ly in layers)

@@ -90,6 +90,22 @@ int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const fl
                  int n, int h_in, int w_in, int stride, int pad,
                  pconv_layout layout, pconv_dtype act_dtype, int fuse_relu, void *hip_stream);
 
+/*
+ * pconv_conv2d_pool2x2 - pconv_conv2d (stride 1, pad 1) followed by a 2x2 / stride-2 max-pool,
+ * in one kernel: y_dev receives [n][c_out][h_in/2][w_in/2] (floor), the full-size convolution
+ * output is never written.  Max-pooling is not part of the paper's method; VGG-16 has one
+ * after five of its thirteen 3x3 layers, and there this saves writing and re-reading the
+ * largest tensors of the network.  Values are those of pconv_conv2d followed by
+ * pconv_maxpool2x2 (bit for bit when both add the input channels in the same order; for layers
+ * with few tiles pconv_conv2d may add them in a different order).  Arguments as for pconv_conv2d.
+ *
+ * Errors: as pconv_conv2d, and PCONV_UNSUPPORTED unless the tensors are fp32 NCHW with
+ * w_in even and >= 4 and h_in >= 2 (and the kernel policy is not 1).
+ */
+int pconv_conv2d_pool2x2(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
+                         int n, int h_in, int w_in, pconv_layout layout, pconv_dtype act_dtype,
+                         int fuse_relu, void *hip_stream);
+
 /* pconv_free - releases the handle's host and device memory.  NULL is allowed. */
 void pconv_free(pconv_handle *h);
 

@@ -58,6 +58,8 @@ def lib():
     L.pconv_debug_pack_host.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, C.POINTER(vp)]
     L.pconv_conv2d.restype = ip
     L.pconv_conv2d.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, ip, ip, vp]
+    L.pconv_conv2d_pool2x2.restype = ip
+    L.pconv_conv2d_pool2x2.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, vp]
     L.pconv_free.restype = None
     L.pconv_free.argtypes = [vp]
     L.pconv_maxpool2x2.restype = ip
@@ -78,7 +80,7 @@ def lib():
     return L
 
 
-EXPORTED_SYMBOLS = ["pconv_pack", "pconv_conv2d", "pconv_free", "pconv_maxpool2x2",
+EXPORTED_SYMBOLS = ["pconv_pack", "pconv_conv2d", "pconv_conv2d_pool2x2", "pconv_free", "pconv_maxpool2x2",
                     "pconv_get_info", "pconv_debug_export", "pconv_debug_pack_host", "pconv_debug_unpack",
                     "pconv_set_kernel_policy", "pconv_debug_set_tiling", "pconv_last_error"]
 
@@ -140,6 +142,14 @@ def pconv_conv2d(handle: Handle, x_ptr: int, y_ptr: int, bias_ptr, n: int, h_in:
     _check(lib().pconv_conv2d(handle.ptr, x_ptr, y_ptr, bias_ptr or None, n, h_in, w_in, stride, pad,
                               _LAYOUT[layout], _DTYPE[act_dtype], int(bool(fuse_relu)),
                               stream or None))
+
+
+def pconv_conv2d_pool2x2(handle: Handle, x_ptr: int, y_ptr: int, bias_ptr, n: int, h_in: int, w_in: int,
+                         layout=NCHW, act_dtype=F32, fuse_relu: bool = False, stream: int = 0):
+    """Raw-pointer call, one to one with the C entry point."""
+    _check(lib().pconv_conv2d_pool2x2(handle.ptr, x_ptr, y_ptr, bias_ptr or None, n, h_in, w_in,
+                                      _LAYOUT[layout], _DTYPE[act_dtype], int(bool(fuse_relu)),
+                                      stream or None))
 
 
 def pconv_free(handle: Handle):
@@ -207,6 +217,25 @@ def conv2d(handle: Handle, x, bias=None, stride: int = 1, relu: bool = False, la
     stream = torch.cuda.current_stream(x.device).cuda_stream
     pconv_conv2d(handle, x.data_ptr(), y.data_ptr(), bias.data_ptr() if bias is not None else 0,
                  n, h, w, stride, 1, lay, handle.dtype, relu, stream)
+    return y
+
+
+def conv2d_pool2x2(handle: Handle, x, bias=None, relu: bool = False, out=None):
+    """x: contiguous fp32 NCHW CUDA tensor.  Returns maxpool2x2(conv2d(x)) without the intermediate."""
+    import torch
+    if not x.is_cuda or not x.is_contiguous():
+        raise ValueError("x must be a contiguous CUDA tensor")
+    n, c, h, w = x.shape
+    if c != handle.c_in:
+        raise ValueError("channel count does not match the handle")
+    if x.dtype != _torch_dtype(handle.dtype):
+        raise ValueError("activation dtype does not match the handle")
+    y = out if out is not None else torch.empty((n, handle.c_out, h // 2, w // 2), dtype=x.dtype, device=x.device)
+    if bias is not None and (bias.dtype != torch.float32 or not bias.is_cuda):
+        raise ValueError("bias must be a float32 CUDA tensor")
+    stream = torch.cuda.current_stream(x.device).cuda_stream
+    pconv_conv2d_pool2x2(handle, x.data_ptr(), y.data_ptr(), bias.data_ptr() if bias is not None else 0,
+                         n, h, w, NCHW, handle.dtype, relu, stream)
     return y
 
 

@@ -179,9 +179,33 @@ int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const fl
     if (policy == 2 && !can_tile) { set_error("pconv_conv2d: register-tiled kernel not available for this call"); return PCONV_UNSUPPORTED; }
     if (policy != 1 && can_tile)
         return launch_conv_tiled(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, int(layout),
-                                 int(act_dtype), fuse_relu ? 1 : 0, hip_stream);
+                                 int(act_dtype), fuse_relu ? 1 : 0, 0, hip_stream);
     return launch_conv_generic(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, int(layout),
                                int(act_dtype), fuse_relu ? 1 : 0, hip_stream);
+}
+
+int pconv_conv2d_pool2x2(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
+                         int n, int h_in, int w_in, pconv_layout layout, pconv_dtype act_dtype,
+                         int fuse_relu, void *hip_stream)
+{
+    if (!h || !x_dev || !y_dev) { set_error("pconv_conv2d_pool2x2: null pointer argument"); return PCONV_INVALID_ARG; }
+    if (x_dev == y_dev) { set_error("pconv_conv2d_pool2x2: y_dev must not alias x_dev"); return PCONV_INVALID_ARG; }
+    if (n <= 0 || h_in <= 0 || w_in <= 0) { set_error("pconv_conv2d_pool2x2: n, h_in and w_in must be positive"); return PCONV_INVALID_ARG; }
+    if (layout != PCONV_NCHW && layout != PCONV_NHWC) { set_error("pconv_conv2d_pool2x2: unknown layout"); return PCONV_INVALID_ARG; }
+    if (h->device < 0) { set_error("pconv_conv2d_pool2x2: handle was packed on the host only and holds no device data"); return PCONV_INVALID_ARG; }
+    if (int(act_dtype) != h->wdtype) { set_error("pconv_conv2d_pool2x2: act_dtype differs from the handle's weight dtype"); return PCONV_INVALID_ARG; }
+    const int64_t lim = (int64_t(1) << 31) - 1;
+    if (int64_t(n) * h->c_in * h_in * w_in > lim || int64_t(n) * h->c_out * h_in * w_in > lim) {
+        set_error("pconv_conv2d_pool2x2: tensors of 2^31 elements or more are not supported");
+        return PCONV_INVALID_ARG;
+    }
+    if (g_policy.load() == 1 || !tiled_pool_supported(h, n, h_in, w_in, int(layout), int(act_dtype))) {
+        set_error("pconv_conv2d_pool2x2: needs the register-tiled kernel with fp32 NCHW tensors of even width >= 4 "
+                  "and height >= 2; use pconv_conv2d and pconv_maxpool2x2");
+        return PCONV_UNSUPPORTED;
+    }
+    return launch_conv_tiled(h, x_dev, y_dev, bias_dev, n, h_in, w_in, 1, int(layout), int(act_dtype),
+                             fuse_relu ? 1 : 0, 1, hip_stream);
 }
 
 int pconv_maxpool2x2(const void *x_dev, void *y_dev, int n, int c, int h, int w,

@@ -80,7 +80,9 @@ void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int 
 int launch_conv_generic(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
                         int hin, int win, int stride, int layout, int dtype, int relu, void *stream);
 int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
-                      int hin, int win, int stride, int layout, int dtype, int relu, void *stream);
+                      int hin, int win, int stride, int layout, int dtype, int relu, int pool, void *stream);
+// whether the tiled kernel can write the 2x2 max-pooled output directly (pool = 1)
+bool tiled_pool_supported(const pconv_handle *h, int n, int hin, int win, int layout, int dtype);
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype);
 // Test override of the tiled kernel's launch choices: waves per workgroup (8 or 16, anything else =
 // automatic), log2 of the channel split inside a workgroup (0..2, anything else = automatic), and

@@ -80,6 +80,7 @@ struct TiledArgs {
     int py, px;                 // patches per image column / row
     int n_patches, n_tiles, n_groups, n_blocks;
     int relu;
+    int pool;                   // 1: y is the 2x2 / stride-2 max-pooled output (VEC kernel, whole units only)
     int ks_log2;                // log2 of the channel split inside a workgroup (0, 1 or 2)
     int n_units;                // n_tiles * n_groups: (tile, filter group) pairs
     int n_chunks;               // chunks of CH input channels
@@ -568,6 +569,26 @@ conv_tiled_kernel(const TiledArgs a)
                 if (f < 0) continue;
                 const float b = (a.bias && !hands_on) ? a.bias[f] : 0.0f;
                 if constexpr (VEC) {
+                    if (a.pool) {
+                        // 2x2 / stride-2 max-pool of the lane's 4x4 outputs (the patch is aligned to the
+                        // pooling grid: rows at multiples of 4, columns at a multiple of 4 or at W - 4
+                        // with W even): two rows of two pooled values.  Bias and ReLU first.
+                        const int hp = ho >> 1, wp = wo >> 1;
+#pragma unroll
+                        for (int i = 0; i < 2; ++i) {
+                            if ((ye >> 1) + i >= hp) continue;
+                            float m[2];
+#pragma unroll
+                            for (int k = 0; k < 2; ++k) {
+                                float v = fmaxf(fmaxf(acc[s][(2 * i) * 4 + 2 * k], acc[s][(2 * i) * 4 + 2 * k + 1]),
+                                                fmaxf(acc[s][(2 * i + 1) * 4 + 2 * k], acc[s][(2 * i + 1) * 4 + 2 * k + 1])) + b;
+                                m[k] = a.relu ? fmaxf(v, 0.0f) : v;
+                            }
+                            float *dst = reinterpret_cast<float *>(y) + ((size_t(n_e) * a.c_out + f) * hp + (ye >> 1) + i) * wp + (xe >> 1);
+                            *reinterpret_cast<float2 *>(dst) = make_float2(m[0], m[1]);
+                        }
+                        continue;
+                    }
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         if (ye + i >= ho) continue;
@@ -659,8 +680,14 @@ bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride,
     return patches < (int64_t(1) << 30);
 }
 
+bool tiled_pool_supported(const pconv_handle *h, int n, int hin, int win, int layout, int dtype)
+{
+    return tiled_supported(h, n, hin, win, 1, layout, dtype) && dtype == PCONV_F32 && layout == PCONV_NCHW &&
+           win >= 4 && win % 2 == 0 && hin >= 2;
+}
+
 int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
-                      int hin, int win, int stride, int layout, int dtype, int relu, void *stream)
+                      int hin, int win, int stride, int layout, int dtype, int relu, int pool, void *stream)
 {
     (void)stride;
     TiledArgs a;
@@ -672,7 +699,7 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     a.n_patches = n * a.py * a.px;
     a.n_tiles = (a.n_patches + 63) / 64;
     a.n_blocks = h->tiled.num_blocks;
-    a.relu = relu;
+    a.relu = relu; a.pool = pool;
     const bool vec = dtype == PCONV_F32 && layout == PCONV_NCHW && win >= 4;
     // Shape: 16-wave workgroups, one per compute unit.  A layer whose input channels fit one 4-channel
     // chunk is all staging and output stores: there two 8-wave workgroups per compute unit overlap
@@ -687,8 +714,9 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     const int slots = cus * (16 / nw);                   // workgroups that can run at once
     // Sharing units costs every workgroup a second start-up and a pass of the partial sums through
     // memory: it pays where whole units would leave half of the compute units or more without work.
-    a.split_units = vec && int64_t(a.n_tiles) * ((a.n_blocks + nw - 1) / nw) <= slots / 2;
-    if (g_force_split >= 0) a.split_units = vec ? g_force_split : 0;
+    // (Not with a fused max-pool: the partial sums need the full-size output tensor.)
+    a.split_units = vec && !pool && int64_t(a.n_tiles) * ((a.n_blocks + nw - 1) / nw) <= slots / 2;
+    if (g_force_split >= 0) a.split_units = (vec && !pool) ? g_force_split : 0;
     a.ks_log2 = 0;
     if (!a.split_units)
         while (a.ks_log2 < 2 && int64_t(a.n_tiles) * ((a.n_blocks + (nw >> a.ks_log2) - 1) / (nw >> a.ks_log2)) <= slots / 2)

@@ -198,6 +198,68 @@ def test_degenerate_filters_and_mixed_masks(policy):
     check_full(spec, L, x, "f32", relu=False, policy=policy, what="empty layer")
 
 
+POOL_SHAPES = [  # (n, c_in, c_out, h, w): even widths; odd and tiny heights; several tiles and filter groups
+    (2, 16, 70, 14, 14), (1, 37, 64, 28, 28), (3, 8, 9, 7, 6), (1, 5, 130, 2, 4), (2, 24, 16, 9, 34), (1, 3, 64, 32, 32),
+]
+
+
+@pytest.mark.parametrize("waves,ks_log2", [(0, -1), (8, 0), (16, 1), (16, 2)])
+def test_fused_maxpool_equals_conv_then_pool(waves, ks_log2):
+    """pconv_conv2d_pool2x2 against the oracle's convolution followed by its max-pool; a pooled
+    value may be off by what the largest of its four inputs may be off."""
+    import torch
+    # (units are not shared between workgroups here, which the fused call never does either: then
+    # the two ways add in the same order and must agree bit for bit)
+    P.pconv_debug_set_tiling(waves, ks_log2, 0)
+    for j, (n, ci, co, h, w) in enumerate(POOL_SHAPES):
+        spec = LayerSpec(f"pool{j}", n, ci, co, h, w, num_patterns=12, pattern_dist="uniform",
+                         keep_div=2.0, count_dist="bernoulli")
+        L = make_layer(spec, 3000 + j); x = make_input(spec, 3000 + j)
+        for relu in (False, True):
+            say(f"[case] pool{j} waves={waves} ks={ks_log2} relu={relu} x={x.shape}")
+            hd = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
+            b = torch.from_numpy(L["bias"]).cuda()
+            y = P.conv2d_pool2x2(hd, to_device(x, "f32"), b, relu=relu)
+            torch.cuda.synchronize()
+            yr, sr = oracle_full(L, x, "f32", "nchw", 1, relu, True)
+            pr = oracle.maxpool2x2(yr.astype(np.float32)).astype(np.float64)
+            # reference pooled in fp64 to keep the comparison exact
+            hh, ww = h // 2, w // 2
+            pr = yr[:, :, :2 * hh, :2 * ww].reshape(n, co, hh, 2, ww, 2).max(axis=(3, 5))
+            ps = sr[:, :, :2 * hh, :2 * ww].reshape(n, co, hh, 2, ww, 2).max(axis=(3, 5))
+            assert tuple(y.shape) == pr.shape
+            assert_close(y.cpu().numpy().astype(np.float64), pr, ps, "f32", f"pool{j}")
+            # and bit for bit what the two separate calls give
+            y2 = P.maxpool2x2(P.conv2d(hd, to_device(x, "f32"), b, relu=relu))
+            torch.cuda.synchronize()
+            assert torch.equal(y, y2), f"pool{j}: fused and separate results differ"
+            hd.free()
+
+
+def test_fused_maxpool_rejects_what_it_cannot_do():
+    import torch
+    spec = LayerSpec("poolerr", 1, 4, 8, 6, 7, num_patterns=12)
+    L = make_layer(spec, 7)
+    hd = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
+    x = torch.zeros((1, 4, 6, 7), device="cuda"); y = torch.zeros((1, 8, 3, 3), device="cuda")
+    with pytest.raises(P.PconvError) as e:
+        P.pconv_conv2d_pool2x2(hd, x.data_ptr(), y.data_ptr(), 0, 1, 6, 7)         # odd width
+    assert e.value.status == P.UNSUPPORTED
+    x = torch.zeros((1, 6, 8, 4), device="cuda")
+    with pytest.raises(P.PconvError) as e:
+        P.pconv_conv2d_pool2x2(hd, x.data_ptr(), y.data_ptr(), 0, 1, 6, 8, P.NHWC)  # NHWC
+    assert e.value.status == P.UNSUPPORTED
+    P.pconv_set_kernel_policy(1)
+    x = torch.zeros((1, 4, 6, 8), device="cuda")
+    with pytest.raises(P.PconvError) as e:
+        P.pconv_conv2d_pool2x2(hd, x.data_ptr(), y.data_ptr(), 0, 1, 6, 8)         # generic kernel forced
+    assert e.value.status == P.UNSUPPORTED
+    with pytest.raises(P.PconvError) as e:
+        P.pconv_conv2d_pool2x2(hd, 0, y.data_ptr(), 0, 1, 6, 8)
+    assert e.value.status == P.INVALID_ARG
+    hd.free()
+
+
 def test_dense_mask_equals_library_conv():
     """All-ones mask + full connectivity on the GPU against a library dense convolution."""
     import torch
