@@ -154,6 +154,17 @@ int pconv_debug_pack_host(const float *w_dense, const uint8_t *pattern_id, const
                           const uint16_t *table, int num_patterns, int c_out, int c_in,
                           pconv_dtype weight_dtype, pconv_handle **out);
 
+/* pconv_debug_export_blocks - how the register-tiled kernel's work was dealt out by pconv_pack
+ * (workload balance, the purpose of the paper's filter kernel reorder).  Filters are dealt to
+ * blocks of 4 (one block per wave); 16 consecutive blocks are the filters of one workgroup; the
+ * input channels are walked in chunks of 8.  Caller-allocated host arrays:
+ *   slot_filter[4 * B]   filter in each slot of each block, -1 for an empty slot;  B = ceil(c_out / 4)
+ *   records[B][J]        work items ("records": one per kept kernel for masks that are in the
+ *                        kernel's code table, more for other masks) of block b in chunk j;
+ *                        J = ceil(c_in / 8)
+ * Works on handles from pconv_debug_pack_host as well. */
+int pconv_debug_export_blocks(const pconv_handle *h, int32_t *slot_filter, uint32_t *records);
+
 /* pconv_debug_unpack - rebuilds dense masked weights [c_out][c_in][3][3] fp32 on the host
  * from the DEVICE copy of the packed data (zeros where nothing is stored). */
 int pconv_debug_unpack(const pconv_handle *h, float *w_dense_out);

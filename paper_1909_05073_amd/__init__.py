@@ -68,6 +68,8 @@ def lib():
     L.pconv_get_info.argtypes = [vp, C.POINTER(pconv_info)]
     L.pconv_debug_export.restype = ip
     L.pconv_debug_export.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.pconv_debug_export_blocks.restype = ip
+    L.pconv_debug_export_blocks.argtypes = [vp, vp, vp]
     L.pconv_debug_unpack.restype = ip
     L.pconv_debug_unpack.argtypes = [vp, vp]
     L.pconv_set_kernel_policy.restype = ip
@@ -81,7 +83,8 @@ def lib():
 
 
 EXPORTED_SYMBOLS = ["pconv_pack", "pconv_conv2d", "pconv_conv2d_pool2x2", "pconv_free", "pconv_maxpool2x2",
-                    "pconv_get_info", "pconv_debug_export", "pconv_debug_pack_host", "pconv_debug_unpack",
+                    "pconv_get_info", "pconv_debug_export", "pconv_debug_export_blocks", "pconv_debug_pack_host",
+                    "pconv_debug_unpack",
                     "pconv_set_kernel_policy", "pconv_debug_set_tiling", "pconv_last_error"]
 
 
@@ -168,6 +171,15 @@ def pconv_set_kernel_policy(policy: int):
 
 def pconv_debug_set_tiling(waves: int = 0, ks_log2: int = -1, split_units: int = -1):
     _check(lib().pconv_debug_set_tiling(int(waves), int(ks_log2), int(split_units)))
+
+
+def pconv_debug_export_blocks(handle: Handle):
+    """(slot_filter [B][4] int32, records [B][J] uint32): see include/pconv.h."""
+    info = handle.info()
+    b, j = -(-info.c_out // 4), -(-info.c_in // 8)
+    slot_filter = np.empty((b, 4), np.int32); records = np.empty((b, j), np.uint32)
+    _check(lib().pconv_debug_export_blocks(handle.ptr, slot_filter.ctypes.data, records.ctypes.data))
+    return slot_filter, records
 
 
 def pconv_debug_export(handle: Handle) -> dict:

@@ -6,6 +6,7 @@
 #include <new>
 
 #include "pconv_internal.h"
+#include "pconv_tiled_codes.h"
 
 namespace pconv {
 
@@ -235,6 +236,18 @@ int pconv_debug_export(const pconv_handle *h, uint16_t *perm, uint32_t *row_ptr,
         uint16_t *o = static_cast<uint16_t *>(vals);
         for (size_t i = 0; i < c.vals_bits.size(); ++i) o[i] = uint16_t(c.vals_bits[i] >> 16);
     }
+    return PCONV_OK;
+}
+
+int pconv_debug_export_blocks(const pconv_handle *h, int32_t *slot_filter, uint32_t *records)
+{
+    if (!h || !slot_filter || !records) { set_error("pconv_debug_export_blocks: null pointer argument"); return PCONV_INVALID_ARG; }
+    const int nb = h->tiled.num_blocks, row = h->tiled.row_len, chunks = (row - 1) / kTileCH;
+    std::memcpy(slot_filter, h->tiled.slot_filter.data(), size_t(nb) * kTileFB * sizeof(int32_t));
+    for (int b = 0; b < nb; ++b)
+        for (int j = 0; j < chunks; ++j)
+            records[size_t(b) * chunks + j] = h->tiled.chan_ptr[size_t(b) * row + (j + 1) * kTileCH] -
+                                              h->tiled.chan_ptr[size_t(b) * row + j * kTileCH];
     return PCONV_OK;
 }
 

@@ -111,3 +111,51 @@ def test_host_only_handle_rejects_compute_and_policy_checks():
         P.pconv_set_kernel_policy(9)
     P.pconv_set_kernel_policy(0)
     h.free()
+
+
+def test_blocks_are_a_balanced_deal_of_all_filters():
+    """Workload balance of the tiled stream: every filter in exactly one slot, record counts add up,
+    and inside every workgroup (16 blocks) no exchange of two filters between blocks lowers
+    sum_b [ sum_j L(b,j)^2 + (sum_j L(b,j))^2 / J ]  (L = records of block b in chunk j),
+    which is what the packer's local search minimises."""
+    for seed, (f, c) in enumerate([(64, 64), (96, 40), (130, 23), (7, 9)]):
+        spec = LayerSpec(f"bal{seed}", 1, c, f, 8, 8, num_patterns=12, pattern_dist="uniform",
+                         keep_div=3.0, count_dist="bernoulli")
+        L = make_layer(spec, 4000 + seed)
+        h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32", host_only=True)
+        slot_filter, records = P.pconv_debug_export_blocks(h)
+        h.free()
+        used = slot_filter[slot_filter >= 0]
+        assert sorted(used.tolist()) == list(range(f))
+        conn = L["conn"].astype(bool)
+        J = records.shape[1]
+        cpad = J * 8
+        per_filter = np.zeros((f, J), np.int64)      # one record per kept kernel: all 12 masks are codes
+        for j in range(J):
+            per_filter[:, j] = conn[:, 8 * j:min(8 * j + 8, c)].sum(axis=1)
+        want = np.zeros_like(records, dtype=np.int64)
+        for b in range(slot_filter.shape[0]):
+            for flt in slot_filter[b]:
+                if flt >= 0:
+                    want[b] += per_filter[flt]
+        assert np.array_equal(records.astype(np.int64), want)
+
+        def cost(load):                               # times J, in integers
+            return int((load ** 2).sum() * J + (load.sum(axis=1) ** 2).sum())
+        nb = slot_filter.shape[0]
+        for g0 in range(0, nb, 16):
+            blocks = range(g0, min(g0 + 16, nb))
+            load = want[g0:g0 + 16].copy()
+            base = cost(load)
+            slots = [(b, s) for b in blocks for s in range(4)]
+            for ia, (ba, sa) in enumerate(slots):
+                for (bb, sb) in slots[ia + 1:]:
+                    if ba == bb:
+                        continue
+                    fa, fb = slot_filter[ba, sa], slot_filter[bb, sb]
+                    ca = per_filter[fa] if fa >= 0 else np.zeros(J, np.int64)
+                    cb = per_filter[fb] if fb >= 0 else np.zeros(J, np.int64)
+                    trial = load.copy()
+                    trial[ba - g0] += cb - ca
+                    trial[bb - g0] += ca - cb
+                    assert cost(trial) >= base, (seed, ba, sa, bb, sb)
