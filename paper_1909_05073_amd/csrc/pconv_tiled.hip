@@ -3,10 +3,10 @@
 // Work decomposition.  A workgroup of NW waves owns 64 "patches" (a patch = a 4x4 block of output
 // pixels of one image; one patch per lane) and 4 * NW filters (4 per wave, its "slots").  Two shapes
 // are built: 16 waves with 8-channel chunks (one workgroup fills a compute unit), and 8 waves with
-// 4-channel chunks (two workgroups share a compute unit, which evens out layers whose workgroup
-// count is a poor multiple of the 256 compute units).  Either way a SIMD runs 4 waves: a single
-// wave issues a vector instruction only about every 6.5 cycles, so it takes three to four of them
-// to keep a SIMD busy.
+// 4-channel chunks (two workgroups share a compute unit; used for layers with at most 4 input
+// channels, where one workgroup's output stores overlap with the other's loads).  Either way a SIMD
+// runs 4 waves: a single wave issues a vector instruction only about every 6.5 cycles, so it takes
+// three to four of them to keep a SIMD busy.
 //
 // The input channels are walked in chunks of CH through two LDS buffers.  For a chunk, the 6x6 input
 // neighbourhood of every patch is staged into LDS (zero outside the image, so the inner loops have

@@ -72,7 +72,7 @@ def resnet50_conv3x3_shapes():
 
 
 def config_layers(config_index: int, batch: int | None = None) -> List[LayerSpec]:
-    """Layer list of benchmark configuration 1..5 (BASELINE configs[0..4])."""
+    """Layer list of benchmark configuration 1..5."""
     if config_index == 1:
         return [LayerSpec("c1_16x16", batch or 1, 16, 16, 16, 16, num_patterns=8,
                           pattern_dist="uniform", keep_div=2.0, count_dist="bernoulli",
