@@ -51,8 +51,9 @@ template <int NW, int CH> struct Shape {
     static constexpr int OFF_INV = OFF_W + WLDS_FLOATS;
     static constexpr int OFF_SYNC = OFF_INV + INV_FLOATS;
     static constexpr int OFF_HALO = OFF_SYNC + SYNC_WORDS;
-    // 16 waves x 8 channels: 159264 of the compute unit's 163840 bytes; 8 x 4: 81440 (two fit)
-    static constexpr size_t LDS_BYTES = size_t(OFF_HALO + HALO_TAB_WORDS) * 4;
+    // 16 waves x 8 channels: 159776 of the compute unit's 163840 bytes; 8 x 4: 81696 (two fit)
+    static constexpr int OFF_OUT = OFF_HALO + HALO_TAB_WORDS;   // per wave: {filter, bias} of its four slots
+    static constexpr size_t LDS_BYTES = size_t(OFF_OUT + NW * 2 * FB) * 4;
     static constexpr int UNITS = 2 * CH;                       // staging units of half a channel per chunk
     static constexpr int SEGS = CH * 6 / NW;                   // (channel, row) segments per wave (register path)
     static_assert(CH * 6 % NW == 0 && UNITS % 8 == 0 && CH <= kTileCH && kTileCH % CH == 0, "unsupported shape");
@@ -197,6 +198,15 @@ conv_tiled_kernel(const TiledArgs a)
         int win_base = c_begin;
         uint32_t ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, ptr_max)];
         uint32_t ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, ptr_max)];
+        // The epilogue needs each slot's filter index and bias: two dependent loads, started here and
+        // parked in LDS so that they cost the epilogue nothing (and no registers in between).
+        float *out_tab = lds + S::OFF_OUT + wave * (2 * FB);
+        if (lane < FB) {
+            const int f = active ? a.slot_filter[fblk * FB + lane] : -1;
+            const float b = (a.bias && f >= 0) ? a.bias[f] : 0.0f;
+            out_tab[2 * lane] = __int_as_float(f);
+            out_tab[2 * lane + 1] = b;
+        }
 
 
         // this lane's patch
@@ -565,9 +575,9 @@ conv_tiled_kernel(const TiledArgs a)
             const int ho = a.h, wo = a.w;
 #pragma unroll
             for (int s = 0; s < FB; ++s) {
-                const int f = a.slot_filter[fblk * FB + s];
+                const int f = __float_as_int(out_tab[2 * s]);
                 if (f < 0) continue;
-                const float b = (a.bias && !hands_on) ? a.bias[f] : 0.0f;
+                const float b = hands_on ? 0.0f : out_tab[2 * s + 1];
                 if constexpr (VEC) {
                     if (a.pool) {
                         // 2x2 / stride-2 max-pool of the lane's 4x4 outputs (the patch is aligned to the
