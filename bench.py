@@ -30,6 +30,9 @@ def main():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--policy", type=int, default=0, help="kernel policy (0 auto, 1 generic, 2 tiled)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--num-patterns", type=int, default=0, choices=[0, 4, 8, 12],
+                    help="size of the pattern table of the sparse layers (0 = the workload's own, 8): the "
+                         "paper's pattern-count experiment on the same shapes")
     ap.add_argument("--no-fuse-pool", action="store_true",
                     help="run every max-pool as a kernel of its own instead of in the epilogue of the convolution")
     ap.add_argument("--profile-copy-mb", type=int, default=0,
@@ -54,6 +57,9 @@ def main():
     P.pconv_set_kernel_policy(args.policy)
     dev = torch.device("cuda:0")
     specs = config_layers(3, batch=args.batch)
+    if args.num_patterns:
+        import dataclasses
+        specs = [s if s.pattern_dist == "dense" else dataclasses.replace(s, num_patterns=args.num_patterns) for s in specs]
     n = args.batch
 
     layers = []
@@ -140,12 +146,13 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"vgg16_3x3_stack_13conv_batch{n}_fp32_8pattern_conn3.6x",
+        "config": {"workload": f"vgg16_3x3_stack_13conv_batch{n}_fp32_{args.num_patterns or 8}pattern_conn3.6x",
                    "global_batch": n, "layout": "nchw", "kernel_policy": args.policy,
                    "fused_maxpools": sum(1 for ly in layers if ly["fuse"])},
         "roofline": {"bound": "alu", "achieved": round(achieved, 3), "peak": PEAK_VEC_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_VEC_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES_BATCH32 if (n == 32 and args.policy == 0 and not args.no_fuse_pool) else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES_BATCH32 if (n == 32 and args.policy == 0 and not args.no_fuse_pool
+                                                                   and args.num_patterns in (0, 8)) else None,
                      "algorithmic_flop": total_flop, "algorithmic_bytes": sum(ly["bytes"] for ly in layers),
                      "kernel": "pconv_conv2d / pconv_conv2d_pool2x2 (13 launches per step, summed)",
                      "conv_ms_per_step": round(conv_ms_total, 4),
