@@ -169,6 +169,7 @@ int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const fl
     if (layout != PCONV_NCHW && layout != PCONV_NHWC) { set_error("pconv_conv2d: unknown layout"); return PCONV_INVALID_ARG; }
     if (h->device < 0) { set_error("pconv_conv2d: handle was packed on the host only and holds no device data"); return PCONV_INVALID_ARG; }
     if (int(act_dtype) != h->wdtype) { set_error("pconv_conv2d: act_dtype differs from the handle's weight dtype"); return PCONV_INVALID_ARG; }
+    { int dev = -1; if (hipGetDevice(&dev) == hipSuccess && dev != h->device) { set_error("pconv_conv2d: the handle was packed for another device than the current one"); return PCONV_INVALID_ARG; } }
     const int ho = (h_in - 1) / stride + 1, wo = (w_in - 1) / stride + 1;
     const int64_t lim = (int64_t(1) << 31) - 1;
     if (int64_t(n) * h->c_in * h_in * w_in > lim || int64_t(n) * h->c_out * ho * wo > lim) {
@@ -195,6 +196,7 @@ int pconv_conv2d_pool2x2(const pconv_handle *h, const void *x_dev, void *y_dev, 
     if (layout != PCONV_NCHW && layout != PCONV_NHWC) { set_error("pconv_conv2d_pool2x2: unknown layout"); return PCONV_INVALID_ARG; }
     if (h->device < 0) { set_error("pconv_conv2d_pool2x2: handle was packed on the host only and holds no device data"); return PCONV_INVALID_ARG; }
     if (int(act_dtype) != h->wdtype) { set_error("pconv_conv2d_pool2x2: act_dtype differs from the handle's weight dtype"); return PCONV_INVALID_ARG; }
+    { int dev = -1; if (hipGetDevice(&dev) == hipSuccess && dev != h->device) { set_error("pconv_conv2d_pool2x2: the handle was packed for another device than the current one"); return PCONV_INVALID_ARG; } }
     const int64_t lim = (int64_t(1) << 31) - 1;
     if (int64_t(n) * h->c_in * h_in * w_in > lim || int64_t(n) * h->c_out * h_in * w_in > lim) {
         set_error("pconv_conv2d_pool2x2: tensors of 2^31 elements or more are not supported");

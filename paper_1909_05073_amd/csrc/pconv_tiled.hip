@@ -22,6 +22,7 @@
 // branch per kernel instead of per weight), reached by one computed jump per record.
 #include <hip/hip_runtime.h>
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 
 #include "pconv_internal.h"
@@ -646,13 +647,17 @@ conv_tiled_kernel(const TiledArgs a)
 template <typename T, int LAYOUT, bool VEC, int NW, int CH, bool SPLIT>
 hipError_t launch_shape(const TiledArgs &a, int64_t wgs, hipStream_t st)
 {
-    static bool attr_done = false;       // (set to the same value by every thread that gets here first)
+    // The kernel needs more dynamic LDS than the default limit: raised once per device (the flag is
+    // set to the same value by every thread that gets here first).
+    static std::atomic<bool> attr_done[64];
     constexpr size_t lds_bytes = Shape<NW, CH>::LDS_BYTES;
-    if (!attr_done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) dev = 0;
+    if (dev >= 64 || !attr_done[dev].load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_tiled_kernel<T, LAYOUT, VEC, NW, CH, SPLIT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
         if (e != hipSuccess) return e;
-        attr_done = true;
+        if (dev < 64) attr_done[dev].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((conv_tiled_kernel<T, LAYOUT, VEC, NW, CH, SPLIT>), dim3(unsigned(wgs)), dim3(NW * 64), lds_bytes, st, a);
     return hipGetLastError();
