@@ -104,6 +104,31 @@ def test_config3_vgg_batch32_sampled(idx):
     h.free()
 
 
+@pytest.mark.parametrize("idx", [1, 9])
+def test_config3_vgg_batch32_fused_pool_sampled(idx):
+    """The fused convolution + max-pool launches of the benchmark (batch 32) on sampled pooled
+    outputs: the oracle computes the four convolution outputs under each of them one by one."""
+    import torch
+    spec = config_layers(3, batch=32)[idx]
+    assert spec.pool_after
+    L = make_layer(spec, base_seed(3) + 100 * idx); x = make_input(spec, base_seed(3) + 100 * idx)
+    say(f"[case] {spec.name}+pool N=32 sampled")
+    h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
+    y = P.conv2d_pool2x2(h, to_device(x, "f32"), torch.from_numpy(L["bias"]).cuda(), relu=True)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy().astype(np.float64)
+    wt = oracle.masked_weights(L["w"], L["pattern_id"], L["conn"], L["table"])
+    pp = sample_points(np.random.default_rng(100 + idx), 32, spec.c_out, spec.h // 2, spec.w // 2, 5000)
+    ref = np.full(len(pp), -np.inf); s_ref = np.zeros(len(pp))
+    for dy in (0, 1):
+        for dx in (0, 1):
+            pts = pp.copy(); pts[:, 2] = 2 * pp[:, 2] + dy; pts[:, 3] = 2 * pp[:, 3] + dx
+            yr, sr = oracle.conv2d_points(x, wt, pts.astype(np.int32), L["bias"], relu=True)
+            ref = np.maximum(ref, yr); s_ref = np.maximum(s_ref, sr)
+    assert_close(gather_points(y, pp, "nchw"), ref, s_ref, "f32", spec.name + "+pool")
+    h.free()
+
+
 def test_config4_resnet_bf16():
     """All sixteen ResNet-50 3x3 layers (stride 2 included), bf16 in/out, fp32 accumulate."""
     seen = set()
