@@ -100,7 +100,7 @@ int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const fl
  * with few tiles pconv_conv2d may add them in a different order).  Arguments as for pconv_conv2d.
  *
  * Errors: as pconv_conv2d, and PCONV_UNSUPPORTED unless the tensors are fp32 NCHW with
- * w_in even and >= 4 and h_in >= 2 (and the kernel policy is not 1).
+ * w_in even and >= 4, h_in >= 2 and an input of less than 2 GiB (and the kernel policy is not 1).
  */
 int pconv_conv2d_pool2x2(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
                          int n, int h_in, int w_in, pconv_layout layout, pconv_dtype act_dtype,

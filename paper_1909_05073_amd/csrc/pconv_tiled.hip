@@ -74,6 +74,10 @@ __device__ __forceinline__ void st_act(bf16_t *p, size_t i, float v)
 }
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+// Byte offset that lies beyond any tensor the VEC kernel accepts (at most 2^31 - 1 bytes): a buffer
+// load at such an offset touches no memory and returns zero.
+constexpr uint32_t kOutOfRange = 0x80000000u;
 
 struct TiledArgs {
     const void *x; void *y; const float *bias;
@@ -89,6 +93,7 @@ struct TiledArgs {
     int split_units;            // 1: a workgroup's share of the work may begin and end inside a unit
     uint32_t *flags;            // [gridDim.x] hand-over words of this call (split_units only)
     uint32_t epoch;             // value that marks a hand-over word as set by this call (never 0)
+    uint32_t x_bytes;           // size of the input tensor (VEC kernel: below 2^31)
 };
 
 template <typename T, int LAYOUT>
@@ -141,6 +146,15 @@ conv_tiled_kernel(const TiledArgs a)
     const T *__restrict__ x = static_cast<const T *>(a.x);
     T *__restrict__ y = static_cast<T *>(a.y);
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
+    // buffer resource of the input tensor (VEC staging): base, stride 0, size in bytes, raw 32-bit data
+    v4u rsrc;
+    {
+        const uint64_t xa = reinterpret_cast<uint64_t>(a.x);
+        rsrc.x = __builtin_amdgcn_readfirstlane(uint32_t(xa));
+        rsrc.y = __builtin_amdgcn_readfirstlane(uint32_t(xa >> 32) & 0xFFFFu);
+        rsrc.z = __builtin_amdgcn_readfirstlane(a.x_bytes);
+        rsrc.w = 0x00020000u;
+    }
     // (Per-lane values are deliberately recomputed where they are used, from a lane id the
     // compiler cannot see through: only a few vector registers may stay live across the record
     // loop, and a spill reload there would wait for the loads in flight for the next chunk.)
@@ -249,7 +263,7 @@ conv_tiled_kernel(const TiledArgs a)
         // VEC path: the twelve halo values of a patch are fetched by twelve one-word loads per channel,
         // each of which fills 64 consecutive words of the halo blocks: word i of load j belongs to patch
         // 16 * (j % 4) + i / 4 and is its halo value e = 4 * (j / 4) + i % 4.  The element offset of that
-        // value in channel 0 (or -1 outside the image) is the same for every chunk: tabulated once.
+        // value in channel 0, in bytes (or kOutOfRange outside the image), is the same for every chunk: tabulated once.
         if (VEC) {
             for (int t = threadIdx.x; t < HALO_TAB_WORDS; t += NW * 64) {
                 const int j = t >> 6, i = t & 63;
@@ -260,43 +274,45 @@ conv_tiled_kernel(const TiledArgs a)
                 const int xh = min((prem_h % a.px) * 4, a.w - 4);
                 const int ix = e < 6 ? xh - 1 : xh + 4;
                 const bool ok = pidx_h < a.n_patches && iy >= 0 && iy < a.h && ix >= 0 && ix < a.w;
-                halo_tab[t] = ok ? (n_h * a.c_in * a.h + iy) * a.w + ix : -1;
+                halo_tab[t] = ok ? ((n_h * a.c_in * a.h + iy) * a.w + ix) * 4 : int(kOutOfRange);
             }
         }
-        // VEC path: global -> LDS directly, no registers and no vector ALU work.  Lanes whose row (or
-        // halo value) lies outside the image are masked off; their LDS words are zeroed once per
-        // piece and never written, so they stay zero for every chunk.
+        // VEC path: global -> LDS directly, no registers and next to no vector ALU work.  The LDS
+        // words of rows and halo values outside the image are zeroed once per piece and never get
+        // anything but zero, so they stay zero for every chunk.
         // One unit of staging work = half a channel: three rows and six halo loads.
         auto stage_direct = [&](int c0, float *buf, int sunit) {
             const int ln = fresh_lane();
             const int ch = sunit >> 1, half = sunit & 1;
-            const bool cv = c0 + ch < a.c_in;
-            const float *xc = reinterpret_cast<const float *>(x) + (c0 + ch) * hw;
+            if (c0 + ch >= a.c_in) return;                               // (uniform)
+            const uint32_t soff = __builtin_amdgcn_readfirstlane(uint32_t(c0 + ch) * uint32_t(hw) * 4u);
             float *cbuf = buf + ch * CHAN_FLOATS;
             // everything the lane needs from the tables first, so that there is one wait for LDS
             const int lane_off_now = inv[2 * ln];
             const uint32_t vmask = uint32_t(inv[2 * ln + 1]);
-            int off[6];
+            uint32_t off[6];
 #pragma unroll
-            for (int k = 0; k < 6; ++k) off[k] = halo_tab[(6 * half + k) * 64 + ln];
-            // The LDS address of lane 0's element goes to M0 and every lane adds lane * size.  Written
-            // as assembly so that the compiler does not track these loads: it would otherwise wait for
-            // them before the record loop (they are waited for explicitly before they are published).
+            for (int k = 0; k < 6; ++k) off[k] = uint32_t(halo_tab[(6 * half + k) * 64 + ln]);
+            // Buffer loads: address = tensor + soff (channel, uniform) + per-lane byte offset; a lane
+            // whose row or halo value lies outside the image has an offset beyond the buffer's size,
+            // for which the hardware reads nothing and delivers zero.  The LDS address of lane 0's
+            // element goes to M0 and every lane adds lane * size.  Written as assembly so that the
+            // compiler does not track these loads: it would otherwise wait for them before the record
+            // loop (they are waited for explicitly before they are published).
 #pragma unroll
             for (int k = 0; k < 3; ++k) {
                 const int r = 3 * half + k;
-                const float *src = xc + (lane_off_now + r * a.w);
+                const uint32_t voff = ((vmask >> r) & 1u) ? uint32_t(lane_off_now + r * a.w) * 4u : kOutOfRange;
                 const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + r * QUAD_FLOATS));
-                if (cv && ((vmask >> r) & 1u))
-                    asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dwordx4 %0, off" ::"v"(src), "s"(dst_b));
+                asm volatile("s_mov_b32 m0, %1\n s_nop 0\n buffer_load_dwordx4 %0, %2, %3 offen lds"
+                             ::"v"(voff), "s"(dst_b), "s"(rsrc), "s"(soff));
             }
 #pragma unroll
             for (int k = 0; k < 6; ++k) {
                 const int j = 6 * half + k;
-                const float *src = xc + off[k];
                 const uint32_t dst_b = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(cbuf + 6 * QUAD_FLOATS + j * 64));
-                if (cv && off[k] >= 0)
-                    asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dword %0, off" ::"v"(src), "s"(dst_b));
+                asm volatile("s_mov_b32 m0, %1\n s_nop 0\n buffer_load_dword %0, %2, %3 offen lds"
+                             ::"v"(off[k]), "s"(dst_b), "s"(rsrc), "s"(soff));
             }
         };
         // generic path (any layout / dtype / width): through registers, with conversion to fp32;
@@ -698,7 +714,7 @@ bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride,
 bool tiled_pool_supported(const pconv_handle *h, int n, int hin, int win, int layout, int dtype)
 {
     return tiled_supported(h, n, hin, win, 1, layout, dtype) && dtype == PCONV_F32 && layout == PCONV_NCHW &&
-           win >= 4 && win % 2 == 0 && hin >= 2;
+           win >= 4 && win % 2 == 0 && hin >= 2 && int64_t(n) * h->c_in * hin * win * 4 < (int64_t(1) << 31);
 }
 
 int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
@@ -715,7 +731,9 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     a.n_tiles = (a.n_patches + 63) / 64;
     a.n_blocks = h->tiled.num_blocks;
     a.relu = relu; a.pool = pool;
-    const bool vec = dtype == PCONV_F32 && layout == PCONV_NCHW && win >= 4;
+    const int64_t x_bytes = int64_t(n) * h->c_in * hin * win * 4;
+    const bool vec = dtype == PCONV_F32 && layout == PCONV_NCHW && win >= 4 && x_bytes < (int64_t(1) << 31);
+    a.x_bytes = uint32_t(std::min<int64_t>(x_bytes, 0x7FFFFFFF));
     // Shape: 16-wave workgroups, one per compute unit.  A layer whose input channels fit one 4-channel
     // chunk is all staging and output stores: there two 8-wave workgroups per compute unit overlap
     // one's stores with the other's loads.
