@@ -121,12 +121,44 @@ def generate():
     return L
 
 
-def main():
-    out = sys.argv[1]
-    with open(out, "w") as f:
+def generate_takeover():
+    """Adds the partial sums that a predecessor workgroup left in the output tensor to the
+    accumulators: acc[slot][row][0..3] += y[so_slot + voff_row .. + 16 bytes].
+
+    Buffer loads (an offset beyond the tensor reads nothing and returns zero), the eight rows of
+    two slots at a time into the input registers, which are free after the record loop: two round
+    trips to memory in all.  Operands: %[voff0]..%[voff3] per-lane byte offset of row 0..3 of the
+    lane's patch in filter plane 0 (out of range for a row below the image or a lane without a
+    patch), %[rsrc] buffer resource of the output tensor, %[so0]..%[so3] byte offset of each
+    slot's filter plane (SGPRs)."""
+    L = []
+    for pair in range(2):
+        for u in range(2):
+            slot = 2 * pair + u
+            for i in range(4):
+                b = INP - 4 + 16 * u + 4 * i          # v24..v55
+                L.append("buffer_load_dwordx4 v[%d:%d], %%[voff%d], %%[rsrc], %%[so%d] offen" % (b, b + 3, i, slot))
+        L.append("s_waitcnt vmcnt(0)")
+        for u in range(2):
+            slot = 2 * pair + u
+            for e in range(16):
+                a = ACC + 16 * slot + e
+                L.append("v_add_f32 v%d, v%d, v%d" % (a, a, INP - 4 + 16 * u + e))
+    return L
+
+
+def write_inc(path, lines):
+    with open(path, "w") as f:
         f.write("// generated by gen_tiled_compute.py - do not edit\n")
-        for line in generate():
+        for line in lines:
             f.write('"%s\\n"\n' % line)
+
+
+def main():
+    import os
+    out = sys.argv[1]
+    write_inc(out, generate())
+    write_inc(os.path.join(os.path.dirname(out), "pconv_tiled_takeover.inc"), generate_takeover())
 
 
 if __name__ == "__main__":

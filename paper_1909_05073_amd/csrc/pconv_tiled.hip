@@ -94,6 +94,7 @@ struct TiledArgs {
     uint32_t *flags;            // [gridDim.x] hand-over words of this call (split_units only)
     uint32_t epoch;             // value that marks a hand-over word as set by this call (never 0)
     uint32_t x_bytes;           // size of the input tensor (VEC kernel: below 2^31)
+    uint32_t y_bytes;           // size of the output tensor (shared units only: below 2^31)
 };
 
 template <typename T, int LAYOUT>
@@ -583,6 +584,44 @@ conv_tiled_kernel(const TiledArgs a)
 #pragma unroll
                     for (int s = 0; s < FB; ++s) acc[s] = __builtin_nanf("");
                 }
+                // Add what the predecessor left in the output tensor: generated assembly, all loads of
+                // two slots in flight at once (the workgroups that share a unit wait for one another
+                // here, one after the other, so this is on the critical path of the layer).  A lane
+                // without a patch, a row below the image and an empty slot read nothing or something
+                // that is never stored.
+                {
+                    const int lt = fresh_lane();
+                    const int pidx_t = tile * 64 + lt;
+                    const bool pv = pidx_t < a.n_patches;
+                    const int n_t = pv ? pidx_t / per_img : 0, prem_t = pv ? pidx_t - n_t * per_img : 0;
+                    const int ye_t = (prem_t / a.px) * 4, xe_t = min((prem_t % a.px) * 4, a.w - 4);
+                    uint32_t voff[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        voff[i] = (pv && ye_t + i < a.h) ? uint32_t(((n_t * a.c_out * a.h + ye_t + i) * a.w) + xe_t) * 4u : kOutOfRange;
+                    uint32_t so[FB];
+#pragma unroll
+                    for (int s = 0; s < FB; ++s) {
+                        const int f = __builtin_amdgcn_readfirstlane(__float_as_int(out_tab[2 * s]));
+                        so[s] = uint32_t(max(f, 0)) * uint32_t(hw) * 4u;
+                    }
+                    v4u yrsrc;
+                    {
+                        const uint64_t ya = reinterpret_cast<uint64_t>(a.y);
+                        yrsrc.x = __builtin_amdgcn_readfirstlane(uint32_t(ya));
+                        yrsrc.y = __builtin_amdgcn_readfirstlane(uint32_t(ya >> 32) & 0xFFFFu);
+                        yrsrc.z = __builtin_amdgcn_readfirstlane(a.y_bytes);
+                        yrsrc.w = 0x00020000u;
+                    }
+                    asm volatile(
+#include "pconv_tiled_takeover.inc"
+                        : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
+                        : [voff0] "v"(voff[0]), [voff1] "v"(voff[1]), [voff2] "v"(voff[2]), [voff3] "v"(voff[3]),
+                          [rsrc] "s"(yrsrc), [so0] "s"(so[0]), [so1] "s"(so[1]), [so2] "s"(so[2]), [so3] "s"(so[3])
+                        : "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33", "v34", "v35",
+                          "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47",
+                          "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "memory");
+                }
             }
         }
         if (writer) {
@@ -623,10 +662,6 @@ conv_tiled_kernel(const TiledArgs a)
                         float o[4];
 #pragma unroll
                         for (int k = 0; k < 4; ++k) o[k] = acc[s][i * 4 + k];
-                        if (takes_over) {
-                            const float4 p = *reinterpret_cast<const float4 *>(dst);
-                            o[0] += p.x; o[1] += p.y; o[2] += p.z; o[3] += p.w;
-                        }
                         if (!hands_on) {
 #pragma unroll
                             for (int k = 0; k < 4; ++k) { o[k] += b; if (a.relu) o[k] = fmaxf(o[k], 0.0f); }
@@ -748,8 +783,12 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     // Sharing units costs every workgroup a second start-up and a pass of the partial sums through
     // memory: it pays where whole units would leave half of the compute units or more without work.
     // (Not with a fused max-pool: the partial sums need the full-size output tensor.)
-    a.split_units = vec && !pool && int64_t(a.n_tiles) * ((a.n_blocks + nw - 1) / nw) <= slots / 2;
-    if (g_force_split >= 0) a.split_units = (vec && !pool) ? g_force_split : 0;
+    // (and needs an output below 2 GiB: the partial sums are read back with range-checked buffer loads)
+    const int64_t y_bytes = int64_t(n) * h->c_out * hin * win * 4;
+    const bool can_split = vec && !pool && y_bytes < (int64_t(1) << 31);
+    a.y_bytes = uint32_t(std::min<int64_t>(y_bytes, 0x7FFFFFFF));
+    a.split_units = can_split && int64_t(a.n_tiles) * ((a.n_blocks + nw - 1) / nw) <= slots / 2;
+    if (g_force_split >= 0) a.split_units = can_split ? g_force_split : 0;
     a.ks_log2 = 0;
     if (!a.split_units)
         while (a.ks_log2 < 2 && int64_t(a.n_tiles) * ((a.n_blocks + (nw >> a.ks_log2) - 1) / (nw >> a.ks_log2)) <= slots / 2)
