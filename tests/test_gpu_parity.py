@@ -129,6 +129,36 @@ def test_config3_vgg_batch32_fused_pool_sampled(idx):
     h.free()
 
 
+@pytest.mark.parametrize("w", [32760, 32776])
+def test_input_just_below_and_above_2_gib(w):
+    """The fp32 NCHW kernel stages with range-checked buffer loads, which address at most 2^31 - 1
+    bytes; a larger input takes the register-staging kernel.  One layer on either side of the
+    limit (2 x 8192 x w floats), on sampled outputs: byte offsets close to 2^31 in the first case,
+    the change of kernels in the second."""
+    import torch
+    n, c_in, c_out, h = 1, 2, 4, 8192
+    nbytes = n * c_in * h * w * 4
+    assert (nbytes < 2**31) == (w == 32760)
+    spec = LayerSpec("limit", n, c_in, c_out, h, w, pattern_dist="uniform", count_dist="all")
+    L = make_layer(spec, 4242)
+    say(f"[case] input of {nbytes} bytes (limit {2**31}), w={w}")
+    rng = np.random.default_rng(77)
+    x = rng.standard_normal((n, c_in, h, w), dtype=np.float32)
+    hd = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
+    y = P.conv2d(hd, torch.from_numpy(x).cuda(), torch.from_numpy(L["bias"]).cuda(), relu=False)
+    torch.cuda.synchronize()
+    pts = sample_points(rng, n, c_out, h, w, 20000)
+    # the last rows and columns as well: the highest addresses of the tensor
+    tail = np.array([(0, f, yy, xx) for f in range(c_out) for yy in (h - 2, h - 1) for xx in range(w - 6, w)], np.int32)
+    pts = np.concatenate([pts, tail])
+    idx = torch.from_numpy(pts.astype(np.int64)).cuda()
+    got = y[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy().astype(np.float64)
+    wt = oracle.masked_weights(L["w"], L["pattern_id"], L["conn"], L["table"])
+    yr, sr = oracle.conv2d_points(x, wt, pts, L["bias"], relu=False)
+    assert_close(got, yr, sr, "f32", f"input of {nbytes} bytes")
+    hd.free()
+
+
 def test_config4_resnet_bf16():
     """All sixteen ResNet-50 3x3 layers (stride 2 included), bf16 in/out, fp32 accumulate."""
     seen = set()
