@@ -179,7 +179,7 @@ int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const fl
     const int policy = g_policy.load();
     const bool can_tile = tiled_supported(h, n, h_in, w_in, stride, int(layout), int(act_dtype));
     if (policy == 2 && !can_tile) { set_error("pconv_conv2d: register-tiled kernel not available for this call"); return PCONV_UNSUPPORTED; }
-    if (policy != 1 && can_tile)
+    if (can_tile && (policy == 2 || (policy == 0 && tiled_preferred(h_in, w_in, stride))))
         return launch_conv_tiled(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, int(layout),
                                  int(act_dtype), fuse_relu ? 1 : 0, 0, hip_stream);
     return launch_conv_generic(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, int(layout),

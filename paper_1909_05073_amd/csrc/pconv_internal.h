@@ -84,6 +84,8 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
 // whether the tiled kernel can write the 2x2 max-pooled output directly (pool = 1)
 bool tiled_pool_supported(const pconv_handle *h, int n, int hin, int win, int layout, int dtype);
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype);
+// whether the automatic policy should take the tiled kernel for a call it supports
+bool tiled_preferred(int hin, int win, int stride);
 // Test override of the tiled kernel's launch choices: waves per workgroup (8 or 16, anything else =
 // automatic), log2 of the channel split inside a workgroup (0..2, anything else = automatic), and
 // whether workgroups may share a unit of work (0 / 1, anything else = automatic).

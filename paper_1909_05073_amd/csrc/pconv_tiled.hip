@@ -87,6 +87,7 @@ struct TiledArgs {
     int n_patches, n_tiles, n_groups, n_blocks;
     int relu;
     int pool;                   // 1: y is the 2x2 / stride-2 max-pooled output (VEC kernel, whole units only)
+    int sub2;                   // 1: stride 2: y holds the outputs at even rows and columns only
     int ks_log2;                // log2 of the channel split inside a workgroup (0, 1 or 2)
     int n_units;                // n_tiles * n_groups: (tile, filter group) pairs
     int n_chunks;               // chunks of CH input channels
@@ -655,6 +656,25 @@ conv_tiled_kernel(const TiledArgs a)
                         }
                         continue;
                     }
+                    if (a.sub2) {
+                        // stride 2: of the lane's 4x4 outputs the two even rows, and of each the two even
+                        // columns (the patch starts at a multiple of 4, or at W - 4 in the last patch of a row)
+                        const int h2 = (ho + 1) >> 1, w2 = (wo + 1) >> 1, k0 = xe & 1;
+#pragma unroll
+                        for (int i = 0; i < 4; i += 2) {
+                            if (ye + i >= ho) continue;
+                            float o[2];
+#pragma unroll
+                            for (int kk = 0; kk < 2; ++kk) {
+                                float v = (k0 ? acc[s][i * 4 + 2 * kk + 1] : acc[s][i * 4 + 2 * kk]) + b;
+                                o[kk] = a.relu ? fmaxf(v, 0.0f) : v;
+                            }
+                            float *dst = reinterpret_cast<float *>(y) + ((size_t(n_e) * a.c_out + f) * h2 + ((ye + i) >> 1)) * w2 + ((xe + k0) >> 1);
+                            dst[0] = o[0];
+                            if (((xe + k0) >> 1) + 1 < w2) dst[1] = o[1];
+                        }
+                        continue;
+                    }
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         if (ye + i >= ho) continue;
@@ -672,12 +692,16 @@ conv_tiled_kernel(const TiledArgs a)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int oy = ye + i;
-                        if (oy >= ho) continue;
+                        if (oy >= ho || (a.sub2 && (oy & 1))) continue;
 #pragma unroll
                         for (int k = 0; k < 4; ++k) {
                             float v = acc[s][i * 4 + k] + b;
                             if (a.relu) v = fmaxf(v, 0.0f);
-                            if (xe + k < wo) st_act(y, act_at<T, LAYOUT>(n_e, f, oy, xe + k, a.c_out, ho, wo), v);
+                            const int ox = xe + k;
+                            if (ox >= wo) continue;
+                            if (!a.sub2) st_act(y, act_at<T, LAYOUT>(n_e, f, oy, ox, a.c_out, ho, wo), v);
+                            else if (!(ox & 1))
+                                st_act(y, act_at<T, LAYOUT>(n_e, f, oy >> 1, ox >> 1, a.c_out, (ho + 1) >> 1, (wo + 1) >> 1), v);
                         }
                     }
                 }
@@ -741,9 +765,18 @@ void set_tiled_tuning(int waves, int ks_log2, int split_units)
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype)
 {
     (void)layout; (void)dtype;
-    if (!h->d_meta || stride != 1) return false;
+    // (stride 2 runs at full resolution and stores every other output)
+    if (!h->d_meta || (stride != 1 && stride != 2)) return false;
     const int64_t patches = int64_t(n) * ((hin + 3) / 4) * ((win + 3) / 4);
     return patches < (int64_t(1) << 30);
+}
+
+bool tiled_preferred(int hin, int win, int stride)
+{
+    // Stride 2 through this kernel computes four times the outputs it stores; measured 1.6 to 3.4
+    // times faster than the gather kernel all the same (ResNet-50 shapes, batch 32, inputs of 56x56,
+    // 28x28 and 14x14).  Smaller images are left to the gather kernel.
+    return stride == 1 || int64_t(hin) * win >= 12 * 12;
 }
 
 bool tiled_pool_supported(const pconv_handle *h, int n, int hin, int win, int layout, int dtype)
@@ -755,8 +788,8 @@ bool tiled_pool_supported(const pconv_handle *h, int n, int hin, int win, int la
 int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
                       int hin, int win, int stride, int layout, int dtype, int relu, int pool, void *stream)
 {
-    (void)stride;
     TiledArgs a;
+    a.sub2 = stride == 2;
     a.x = x; a.y = y; a.bias = bias;
     a.slot_filter = h->d_slot_filter; a.chan_ptr = h->d_chan_ptr; a.meta = h->d_meta;
     a.w4 = reinterpret_cast<const float4 *>(h->d_w4);
@@ -785,7 +818,7 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     // (Not with a fused max-pool: the partial sums need the full-size output tensor.)
     // (and needs an output below 2 GiB: the partial sums are read back with range-checked buffer loads)
     const int64_t y_bytes = int64_t(n) * h->c_out * hin * win * 4;
-    const bool can_split = vec && !pool && y_bytes < (int64_t(1) << 31);
+    const bool can_split = vec && !pool && !a.sub2 && y_bytes < (int64_t(1) << 31);
     a.y_bytes = uint32_t(std::min<int64_t>(y_bytes, 0x7FFFFFFF));
     a.split_units = can_split && int64_t(a.n_tiles) * ((a.n_blocks + nw - 1) / nw) <= slots / 2;
     if (g_force_split >= 0) a.split_units = can_split ? g_force_split : 0;

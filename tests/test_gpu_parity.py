@@ -200,7 +200,7 @@ EDGE_SHAPES = [  # (n, c_in, c_out, h, w)
 ]
 
 
-@pytest.mark.parametrize("policy", POLICIES)
+@pytest.mark.parametrize("policy", POLICIES + [2])      # 2 = register-tiled kernel for every call (small stride-2 layers too)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("layout", ["nchw", "nhwc"])
 @pytest.mark.parametrize("stride", [1, 2])
@@ -210,6 +210,18 @@ def test_ragged_shapes_layouts_strides(policy, dtype, layout, stride):
                          pattern_dist="uniform", keep_div=2.0, count_dist="bernoulli")
         L = make_layer(spec, 1000 + j); x = make_input(spec, 1000 + j, layout)
         check_full(spec, L, x, dtype, layout, stride, relu=bool(j & 1), use_bias=bool(j & 2), policy=policy)
+
+
+@pytest.mark.parametrize("waves,ks_log2", [(0, -1), (8, 0), (16, 1), (16, 2)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stride2_through_the_tiled_kernel(waves, ks_log2, dtype):
+    """Stride 2 on the register-tiled kernel (full-resolution sums, every other output stored) in
+    every workgroup shape, odd and even sizes, several chunks and filter groups."""
+    for j, (n, ci, co, h, w) in enumerate([(2, 37, 150, 14, 14), (1, 64, 64, 29, 31), (3, 19, 70, 9, 22), (1, 130, 33, 7, 7)]):
+        spec = LayerSpec(f"s2_{j}", n, ci, co, h, w, stride=2, dtype=dtype)
+        L = make_layer(spec, 3000 + j); x = make_input(spec, 3000 + j)
+        P.pconv_debug_set_tiling(waves, ks_log2, -1)
+        check_full(spec, L, x, dtype, "nchw", 2, relu=bool(j & 1), policy=2, what=f"{spec.name} waves={waves} ks={ks_log2}")
 
 
 TILING_SHAPES = [  # (n, c_in, c_out, h, w): several chunks and filter groups, ragged in every dimension
