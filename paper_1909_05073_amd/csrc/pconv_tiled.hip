@@ -180,7 +180,19 @@ conv_tiled_kernel(const TiledArgs a)
         const int64_t iters = int64_t(set_units) * n_chunks;
         const int64_t takers = iters < wgs_in_set ? iters : wgs_in_set;       // nobody gets an empty range in between
         if (j_in_set >= takers) return;
-        const int64_t it0 = iters * j_in_set / takers, it1 = iters * (j_in_set + 1) / takers;
+        int64_t it0 = iters * j_in_set / takers, it1 = iters * (j_in_set + 1) / takers;
+        // When every unit is shared by the same number P of workgroups, those finish their chunks at
+        // the same time and then pass the sums on one after the other, each link of that chain taking
+        // about as long as 2.5 chunks.  Their shares are therefore graded, the first the smallest and
+        // 2.5 chunks more for each successor (boundary k at k n / P - 2.5 k (P - k) / 2), so that a
+        // workgroup finishes about when its predecessor's sums arrive.
+        const int P = int(takers / set_units);
+        if (set_units * P == takers && P >= 2 && 4 * n_chunks >= P * (16 + 5 * (P - 1))) {
+            const int u = j_in_set / P, kk = j_in_set - u * P;
+            auto bound = [&](int q) { return (4 * q * n_chunks / P - 5 * q * (P - q)) / 4; };
+            it0 = int64_t(u) * n_chunks + bound(kk);
+            it1 = int64_t(u) * n_chunks + bound(kk + 1);
+        }
         ua = int(it0 / n_chunks); ub = int((it1 - 1) / n_chunks);            // first and last unit touched
         head_c0 = int(it0 - int64_t(ua) * n_chunks);                         // > 0: unit ua begins elsewhere
         tail_c1 = int(it1 - int64_t(ub) * n_chunks);                         // < n_chunks: unit ub ends elsewhere
