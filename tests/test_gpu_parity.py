@@ -378,6 +378,35 @@ def test_run_to_run_bit_identical_and_stream():
     h.free()
 
 
+def test_concurrent_calls_on_one_handle_with_shared_units():
+    """Two streams run the same handle at the same time on a layer whose workgroups share units
+    (they signal each other through per-call words of the handle): every result must equal, bit
+    for bit, what the same call gives alone."""
+    import torch
+    spec = config_layers(2)[0]                       # 256 -> 256 at 56x56, batch 1: 16 units, shared
+    L = make_layer(spec, base_seed(2))
+    h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
+    b = torch.from_numpy(L["bias"]).cuda()
+    xs = [to_device(make_input(spec, base_seed(2) + 7 * k), "f32") for k in range(2)]
+    refs = [P.conv2d(h, x, b, relu=True).clone() for x in xs]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [[], []]
+    for s in streams:
+        s.wait_stream(torch.cuda.current_stream())
+    say("[case] 2 streams x 12 overlapping calls on one handle")
+    for it in range(12):
+        for k in range(2):
+            with torch.cuda.stream(streams[k]):
+                outs[k].append(P.conv2d(h, xs[k], b, relu=True))
+    for s in streams:
+        s.synchronize()
+    for k in range(2):
+        for it, y in enumerate(outs[k]):
+            assert torch.equal(y, refs[k]), f"stream {k}, call {it}: differs from the call run alone"
+    h.free()
+
+
 def test_gpu_argument_errors():
     import torch
     spec = config_layers(1)[0]
