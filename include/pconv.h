@@ -70,8 +70,16 @@ int pconv_pack(const float *w_dense, const uint8_t *pattern_id, const uint8_t *c
 /*
  * pconv_conv2d - the sparse convolution itself (Eq. (1) over the packed weights; the
  * "load redundancy elimination" stage of the paper: only inputs under kept taps of kept
- * kernels are touched).  Asynchronous on hip_stream; allocates nothing; the handle is
- * read-only, so concurrent calls on one handle are safe.
+ * kernels are touched).  Asynchronous on hip_stream; allocates nothing.  The packed weights in
+ * the handle are only read.  A call does write two small things that belong to the handle: it
+ * takes a ticket from a call counter, and, when the layer has so few tiles that workgroups share
+ * them, its workgroups signal each other through one of 64 rows of hand-over words in device
+ * memory (row = ticket mod 64).  Calls on one handle may therefore run concurrently on different
+ * streams, as long as no more than 64 such calls are in flight at once.
+ *
+ * Every wait inside the kernels is bounded.  If one ever runs out, the affected outputs are set
+ * to NaN and the handle remembers it: the next pconv_conv2d / pconv_conv2d_pool2x2 on the handle,
+ * or pconv_get_async_error, returns PCONV_HIP_ERROR once (and launches nothing).
  *
  *   x_dev     device, activations [n][c_in][h_in][w_in] (NCHW) or [n][h_in][w_in][c_in]
  *             (NHWC), fp32 or bf16 as act_dtype says.
@@ -84,11 +92,19 @@ int pconv_pack(const float *w_dense, const uint8_t *pattern_id, const uint8_t *c
  *   hip_stream  a hipStream_t, or NULL for the default stream.
  *
  * Errors: PCONV_INVALID_ARG (null pointers, n/h/w <= 0, stride not in {1,2}, pad != 1,
- * dtype mismatch, tensors of 2^31 elements or more), PCONV_HIP_ERROR (launch failed).
+ * dtype mismatch, tensors of 2^31 elements or more), PCONV_HIP_ERROR (launch failed, or an
+ * earlier kernel on this handle gave up a wait: see above).
  */
 int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
                  int n, int h_in, int w_in, int stride, int pad,
                  pconv_layout layout, pconv_dtype act_dtype, int fuse_relu, void *hip_stream);
+
+/*
+ * pconv_get_async_error - PCONV_HIP_ERROR (once, with a message) if a kernel launched on this
+ * handle gave up one of its bounded waits since the last report, else PCONV_OK.  Touches no
+ * device; meaningful after the stream(s) of the calls in question have been synchronised.
+ */
+int pconv_get_async_error(const pconv_handle *h);
 
 /*
  * pconv_conv2d_pool2x2 - pconv_conv2d (stride 1, pad 1) followed by a 2x2 / stride-2 max-pool,
@@ -181,6 +197,13 @@ int pconv_set_kernel_policy(int policy);
  * range of the input channels; -1 = automatic).  Values out of range mean automatic.
  * Process-wide; results are the same for every choice up to the order of the fp32 additions. */
 int pconv_debug_set_tiling(int waves, int ks_log2, int split_units);
+
+/* pconv_debug_set_spin_limit - for tests of the error path: the number of polls after which a
+ * wait inside the register-tiled kernel gives up (limit <= 0 restores the default, about half a
+ * second).  With limit = 1 every such wait gives up at once: the kernels still run to their end,
+ * their outputs are invalid, and the handle reports the error as described at pconv_conv2d.
+ * Process-wide. */
+int pconv_debug_set_spin_limit(int limit);
 
 const char *pconv_last_error(void);
 

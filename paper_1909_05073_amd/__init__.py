@@ -76,6 +76,10 @@ def lib():
     L.pconv_set_kernel_policy.argtypes = [ip]
     L.pconv_debug_set_tiling.restype = ip
     L.pconv_debug_set_tiling.argtypes = [ip, ip, ip]
+    L.pconv_debug_set_spin_limit.restype = ip
+    L.pconv_debug_set_spin_limit.argtypes = [ip]
+    L.pconv_get_async_error.restype = ip
+    L.pconv_get_async_error.argtypes = [vp]
     L.pconv_last_error.restype = C.c_char_p
     L.pconv_last_error.argtypes = []
     _lib = L
@@ -85,7 +89,8 @@ def lib():
 EXPORTED_SYMBOLS = ["pconv_pack", "pconv_conv2d", "pconv_conv2d_pool2x2", "pconv_free", "pconv_maxpool2x2",
                     "pconv_get_info", "pconv_debug_export", "pconv_debug_export_blocks", "pconv_debug_pack_host",
                     "pconv_debug_unpack",
-                    "pconv_set_kernel_policy", "pconv_debug_set_tiling", "pconv_last_error"]
+                    "pconv_set_kernel_policy", "pconv_debug_set_tiling", "pconv_debug_set_spin_limit",
+                    "pconv_get_async_error", "pconv_last_error"]
 
 
 def _check(rc: int):
@@ -171,6 +176,15 @@ def pconv_set_kernel_policy(policy: int):
 
 def pconv_debug_set_tiling(waves: int = 0, ks_log2: int = -1, split_units: int = -1):
     _check(lib().pconv_debug_set_tiling(int(waves), int(ks_log2), int(split_units)))
+
+
+def pconv_debug_set_spin_limit(limit: int = 0):
+    _check(lib().pconv_debug_set_spin_limit(int(limit)))
+
+
+def pconv_get_async_error(handle: Handle):
+    """Raises PconvError(HIP_ERROR) once if a kernel on this handle gave up a bounded wait."""
+    _check(lib().pconv_get_async_error(handle.ptr))
 
 
 def pconv_debug_export_blocks(handle: Handle):

@@ -45,6 +45,20 @@ void release_device(pconv_handle *h)
                     h->d_slot_filter, h->d_chan_ptr, h->d_meta, h->d_w4, h->d_flags};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+    if (h->h_err) (void)hipHostFree(h->h_err);
+    h->h_err = nullptr;
+}
+
+// Reports (once) that a kernel launched earlier on this handle gave up one of its bounded waits.
+int take_async_error(const pconv_handle *h, const char *who)
+{
+    if (!h->h_err) return PCONV_OK;
+    const uint32_t code = __atomic_load_n(h->h_err, __ATOMIC_ACQUIRE);
+    if (code == 0) return PCONV_OK;
+    __atomic_store_n(h->h_err, 0u, __ATOMIC_RELEASE);
+    set_error(std::string(who) + ": an earlier kernel on this handle ran out of a bounded wait (code " +
+              std::to_string(code) + "); the outputs of that call are invalid (NaN where the kernel noticed)");
+    return PCONV_HIP_ERROR;
 }
 
 }  // namespace
@@ -67,6 +81,18 @@ int pconv_debug_set_tiling(int waves, int ks_log2, int split_units)
 {
     set_tiled_tuning(waves, ks_log2, split_units);
     return PCONV_OK;
+}
+
+int pconv_debug_set_spin_limit(int limit)
+{
+    set_tiled_spin_limit(limit);
+    return PCONV_OK;
+}
+
+int pconv_get_async_error(const pconv_handle *h)
+{
+    if (!h) { set_error("pconv_get_async_error: null pointer argument"); return PCONV_INVALID_ARG; }
+    return take_async_error(h, "pconv_get_async_error");
 }
 
 static int pack_impl(const float *w_dense, const uint8_t *pattern_id, const uint8_t *conn,
@@ -113,6 +139,15 @@ static int pack_impl(const float *w_dense, const uint8_t *pattern_id, const uint
             const std::vector<uint32_t> zeros(size_t(kFlagSlots) * kFlagWords, 0u);
             rc = upload(h->d_flags, zeros.data(), zeros.size(), h->device_bytes);
         }
+        if (rc == PCONV_OK) {
+            e = hipHostMalloc(reinterpret_cast<void **>(&h->h_err), 64, hipHostMallocDefault);
+            if (e != hipSuccess) { h->h_err = nullptr; rc = hip_fail("pconv_pack: hipHostMalloc", e); }
+            else std::memset(h->h_err, 0, 64);
+        }
+        if (rc == PCONV_OK) {
+            if (hipDeviceGetAttribute(&h->cus, hipDeviceAttributeMultiprocessorCount, h->device) != hipSuccess || h->cus <= 0)
+                h->cus = 256;
+        }
         if (rc != PCONV_OK) { release_device(h); delete h; return rc; }
     } catch (const std::bad_alloc &) {
         if (h) { release_device(h); delete h; }
@@ -157,9 +192,9 @@ int pconv_get_info(const pconv_handle *h, pconv_info *info)
     return PCONV_OK;
 }
 
-int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
-                 int n, int h_in, int w_in, int stride, int pad, pconv_layout layout,
-                 pconv_dtype act_dtype, int fuse_relu, void *hip_stream)
+static int conv2d_impl(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
+                       int n, int h_in, int w_in, int stride, int pad, pconv_layout layout,
+                       pconv_dtype act_dtype, int fuse_relu, void *hip_stream)
 {
     if (!h || !x_dev || !y_dev) { set_error("pconv_conv2d: null pointer argument"); return PCONV_INVALID_ARG; }
     if (x_dev == y_dev) { set_error("pconv_conv2d: y_dev must not alias x_dev"); return PCONV_INVALID_ARG; }
@@ -176,6 +211,7 @@ int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const fl
         set_error("pconv_conv2d: tensors of 2^31 elements or more are not supported");
         return PCONV_INVALID_ARG;
     }
+    if (const int rc = take_async_error(h, "pconv_conv2d")) return rc;
     const int policy = g_policy.load();
     const bool can_tile = tiled_supported(h, n, h_in, w_in, stride, int(layout), int(act_dtype));
     if (policy == 2 && !can_tile) { set_error("pconv_conv2d: register-tiled kernel not available for this call"); return PCONV_UNSUPPORTED; }
@@ -184,6 +220,14 @@ int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const fl
                                  int(act_dtype), fuse_relu ? 1 : 0, 0, hip_stream);
     return launch_conv_generic(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, int(layout),
                                int(act_dtype), fuse_relu ? 1 : 0, hip_stream);
+}
+
+int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
+                 int n, int h_in, int w_in, int stride, int pad, pconv_layout layout,
+                 pconv_dtype act_dtype, int fuse_relu, void *hip_stream)
+{
+    return conv2d_impl(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, pad, layout, act_dtype, fuse_relu,
+                       hip_stream);
 }
 
 int pconv_conv2d_pool2x2(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
@@ -202,6 +246,7 @@ int pconv_conv2d_pool2x2(const pconv_handle *h, const void *x_dev, void *y_dev, 
         set_error("pconv_conv2d_pool2x2: tensors of 2^31 elements or more are not supported");
         return PCONV_INVALID_ARG;
     }
+    if (const int rc = take_async_error(h, "pconv_conv2d_pool2x2")) return rc;
     if (g_policy.load() == 1 || !tiled_pool_supported(h, n, h_in, w_in, int(layout), int(act_dtype))) {
         set_error("pconv_conv2d_pool2x2: needs the register-tiled kernel with fp32 NCHW tensors of even width >= 4 "
                   "and height >= 2; use pconv_conv2d and pconv_maxpool2x2");

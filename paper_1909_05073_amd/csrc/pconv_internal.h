@@ -65,6 +65,11 @@ struct pconv_handle {
     // value, so calls that overlap on different streams do not see each other's signals.
     uint32_t *d_flags = nullptr;     // [kFlagSlots][kFlagWords], zero at start
     mutable std::atomic<uint32_t> calls{0};
+    // Sticky error word of the kernels launched on this handle: pinned host memory that the device
+    // writes (non-zero = a bounded wait inside a kernel ran out) and that the next call on the
+    // handle reads without touching the device.
+    uint32_t *h_err = nullptr;
+    int cus = 0;                     // compute units of `device`, read once at pack time
 };
 
 namespace pconv {
@@ -90,6 +95,8 @@ bool tiled_preferred(int hin, int win, int stride);
 // automatic), log2 of the channel split inside a workgroup (0..2, anything else = automatic), and
 // whether workgroups may share a unit of work (0 / 1, anything else = automatic).
 void set_tiled_tuning(int waves, int ks_log2, int split_units);
+// Test override of the iteration limit of the kernels' bounded waits (<= 0 restores the default).
+void set_tiled_spin_limit(int limit);
 int launch_maxpool2x2(const void *x, void *y, int n, int c, int h, int w, int layout, int dtype,
                       void *stream);
 

@@ -1,4 +1,4 @@
-// Register-tiled PCONV kernel for gfx950 (stride 1).
+// Register-tiled PCONV kernel for gfx950 (stride 1; stride 2 as stride 1 with every other output stored).
 //
 // Work decomposition.  A workgroup of NW waves owns 64 "patches" (a patch = a 4x4 block of output
 // pixels of one image; one patch per lane) and 4 * NW filters (4 per wave, its "slots").  Two shapes
@@ -96,7 +96,12 @@ struct TiledArgs {
     uint32_t epoch;             // value that marks a hand-over word as set by this call (never 0)
     uint32_t x_bytes;           // size of the input tensor (VEC kernel: below 2^31)
     uint32_t y_bytes;           // size of the output tensor (shared units only: below 2^31)
+    uint32_t *err;              // sticky error word of the handle (host memory the device can write)
+    int spin_limit;             // iterations after which a wait inside the kernel gives up
 };
+
+// Error codes a kernel leaves in the handle's error word.
+constexpr uint32_t kErrChunkWait = 1u, kErrHandOverWait = 2u;
 
 template <typename T, int LAYOUT>
 __device__ __forceinline__ size_t act_at(int n, int c, int y, int x, int C, int H, int W)
@@ -453,13 +458,20 @@ conv_tiled_kernel(const TiledArgs a)
             // itself.  Waits are bounded (kSpinLimit) so that a mistake here ends in wrong results, not
             // in a hang.
             unsigned *tickets = sync_words, *staged = sync_words + 2, *done = sync_words + 4;
-            constexpr int kSpinLimit = 1 << 22;
+            // A wait that runs out marks the workgroup (every wave poisons its outputs with NaN in
+            // the epilogue) and leaves a code in the handle's error word, which the next call on
+            // the handle reports.
             auto wait_ge = [&](unsigned *p, unsigned target) {
-                for (int guard = 0; guard < kSpinLimit; ++guard) {
+                bool reached = false;
+                for (int guard = 0; guard < a.spin_limit; ++guard) {
                     const unsigned v = __builtin_amdgcn_readfirstlane(
                         __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-                    if (v >= target) break;
+                    if (v >= target) { reached = true; break; }
                     __builtin_amdgcn_s_sleep(2);
+                }
+                if (!reached && fresh_lane() == 0) {
+                    __hip_atomic_store(&sync_words[6], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    __hip_atomic_store(a.err, kErrChunkWait, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                 }
             };
             // A wave asks for staging work once per chunk, with one atomic add of kClaim: the counter
@@ -585,18 +597,17 @@ conv_tiled_kernel(const TiledArgs a)
                 // device-wide acquire; the barrier passes it on to the other waves.
                 if (wave == 0) {
                     bool there = false;
-                    for (int guard = 0; guard < (1 << 20) && !there; ++guard) {
+                    for (int guard = 0; guard < (a.spin_limit >> 2) && !there; ++guard) {
                         there = __hip_atomic_load(a.flags + (blockIdx.x - 8), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
                         if (!there) __builtin_amdgcn_s_sleep(8);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-                    if (!there && lane == 0) sync_words[6] = 1u;
+                    if (!there && lane == 0) {
+                        sync_words[6] = 1u;
+                        __hip_atomic_store(a.err, kErrHandOverWait, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                    }
                 }
                 __syncthreads();
-                if (sync_words[6]) {
-#pragma unroll
-                    for (int s = 0; s < FB; ++s) acc[s] = __builtin_nanf("");
-                }
                 // Add what the predecessor left in the output tensor: generated assembly, all loads of
                 // two slots in flight at once (the workgroups that share a unit wait for one another
                 // here, one after the other, so this is on the critical path of the layer).  A lane
@@ -635,6 +646,13 @@ conv_tiled_kernel(const TiledArgs a)
                           "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45", "v46", "v47",
                           "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "memory");
                 }
+            }
+        }
+        if constexpr (VEC) {
+            // a wait of this workgroup ran out: its sums cannot be trusted
+            if (__hip_atomic_load(&sync_words[6], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) {
+#pragma unroll
+                for (int s = 0; s < FB; ++s) acc[s] = __builtin_nanf("");
             }
         }
         if (writer) {
@@ -732,47 +750,50 @@ conv_tiled_kernel(const TiledArgs a)
 }
 
 template <typename T, int LAYOUT, bool VEC, int NW, int CH, bool SPLIT>
-hipError_t launch_shape(const TiledArgs &a, int64_t wgs, hipStream_t st)
+hipError_t launch_shape(const TiledArgs &a, int64_t wgs, hipStream_t st, int dev)
 {
     // The kernel needs more dynamic LDS than the default limit: raised once per device (the flag is
     // set to the same value by every thread that gets here first).
     static std::atomic<bool> attr_done[64];
     constexpr size_t lds_bytes = Shape<NW, CH>::LDS_BYTES;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0) dev = 0;
-    if (dev >= 64 || !attr_done[dev].load(std::memory_order_acquire)) {
+    if (dev < 0 || dev >= 64 || !attr_done[dev].load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_tiled_kernel<T, LAYOUT, VEC, NW, CH, SPLIT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
         if (e != hipSuccess) return e;
-        if (dev < 64) attr_done[dev].store(true, std::memory_order_release);
+        if (dev >= 0 && dev < 64) attr_done[dev].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((conv_tiled_kernel<T, LAYOUT, VEC, NW, CH, SPLIT>), dim3(unsigned(wgs)), dim3(NW * 64), lds_bytes, st, a);
     return hipGetLastError();
 }
 
 template <int NW, int CH>
-hipError_t launch_any(const TiledArgs &a, int64_t wgs, hipStream_t st, bool vec, int layout, int dtype)
+hipError_t launch_any(const TiledArgs &a, int64_t wgs, hipStream_t st, bool vec, int layout, int dtype, int dev)
 {
     if (vec)
-        return a.split_units ? launch_shape<float, PCONV_NCHW, true, NW, CH, true>(a, wgs, st)
-                             : launch_shape<float, PCONV_NCHW, true, NW, CH, false>(a, wgs, st);
+        return a.split_units ? launch_shape<float, PCONV_NCHW, true, NW, CH, true>(a, wgs, st, dev)
+                             : launch_shape<float, PCONV_NCHW, true, NW, CH, false>(a, wgs, st, dev);
     if (dtype == PCONV_F32)
-        return layout == PCONV_NCHW ? launch_shape<float, PCONV_NCHW, false, NW, CH, false>(a, wgs, st)
-                                    : launch_shape<float, PCONV_NHWC, false, NW, CH, false>(a, wgs, st);
-    return layout == PCONV_NCHW ? launch_shape<bf16_t, PCONV_NCHW, false, NW, CH, false>(a, wgs, st)
-                                : launch_shape<bf16_t, PCONV_NHWC, false, NW, CH, false>(a, wgs, st);
+        return layout == PCONV_NCHW ? launch_shape<float, PCONV_NCHW, false, NW, CH, false>(a, wgs, st, dev)
+                                    : launch_shape<float, PCONV_NHWC, false, NW, CH, false>(a, wgs, st, dev);
+    return layout == PCONV_NCHW ? launch_shape<bf16_t, PCONV_NCHW, false, NW, CH, false>(a, wgs, st, dev)
+                                : launch_shape<bf16_t, PCONV_NHWC, false, NW, CH, false>(a, wgs, st, dev);
 }
 
-int g_force_waves = 0, g_force_ks = -1, g_force_split = -1;    // test overrides, see set_tiled_tuning
+// test overrides, see set_tiled_tuning / set_tiled_spin_limit
+std::atomic<int> g_force_waves{0}, g_force_ks{-1}, g_force_split{-1};
+constexpr int kDefaultSpinLimit = 1 << 22;
+std::atomic<int> g_spin_limit{kDefaultSpinLimit};
 
 }  // namespace
 
 void set_tiled_tuning(int waves, int ks_log2, int split_units)
 {
-    g_force_waves = (waves == 8 || waves == 16) ? waves : 0;
-    g_force_ks = (ks_log2 >= 0 && ks_log2 <= 2) ? ks_log2 : -1;
-    g_force_split = (split_units == 0 || split_units == 1) ? split_units : -1;
+    g_force_waves.store((waves == 8 || waves == 16) ? waves : 0);
+    g_force_ks.store((ks_log2 >= 0 && ks_log2 <= 2) ? ks_log2 : -1);
+    g_force_split.store((split_units == 0 || split_units == 1) ? split_units : -1);
 }
+
+void set_tiled_spin_limit(int limit) { g_spin_limit.store(limit > 0 ? limit : kDefaultSpinLimit); }
 
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype)
 {
@@ -817,28 +838,33 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     // Shape: 16-wave workgroups, one per compute unit.  A layer whose input channels fit one 4-channel
     // chunk is all staging and output stores: there two 8-wave workgroups per compute unit overlap
     // one's stores with the other's loads.
-    const int nw = g_force_waves ? g_force_waves : (h->c_in <= 4 ? 8 : 16);
+    const int force_waves = g_force_waves.load(), force_ks = g_force_ks.load(), force_split = g_force_split.load();
+    a.err = h->h_err; a.spin_limit = g_spin_limit.load();
+    const int nw = force_waves ? force_waves : (h->c_in <= 4 ? 8 : 16);
     const int ch = nw == 16 ? 8 : 4;
     a.n_chunks = (h->c_in + ch - 1) / ch;
     // Few units: share them between workgroups (needs fp32 outputs written 128 bits at a time, the
     // VEC kernel), else split the channels inside the workgroups.
-    int cus = 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device) != hipSuccess || cus <= 0) cus = 256;
+    const int cus = h->cus > 0 ? h->cus : 256;
     const int slots = cus * (16 / nw);                   // workgroups that can run at once
     // Sharing units costs every workgroup a second start-up and a pass of the partial sums through
     // memory: it pays where whole units would leave half of the compute units or more without work.
     // (Not with a fused max-pool: the partial sums need the full-size output tensor.)
     // (and needs an output below 2 GiB: the partial sums are read back with range-checked buffer loads)
     const int64_t y_bytes = int64_t(n) * h->c_out * hin * win * 4;
-    const bool can_split = vec && !pool && !a.sub2 && y_bytes < (int64_t(1) << 31);
+    // (and tiles whose borders fall between patch rows: where the image width is no multiple of 4
+    // the last patch of a row overlaps its neighbour, and both write the columns they share; if the
+    // two lay in different tiles, their workgroups would read and overwrite each other's partial sums)
+    const bool rows_whole = win % 4 == 0 || a.n_tiles == 1 || 64 % a.px == 0;
+    const bool can_split = vec && !pool && !a.sub2 && y_bytes < (int64_t(1) << 31) && rows_whole;
     a.y_bytes = uint32_t(std::min<int64_t>(y_bytes, 0x7FFFFFFF));
     a.split_units = can_split && int64_t(a.n_tiles) * ((a.n_blocks + nw - 1) / nw) <= slots / 2;
-    if (g_force_split >= 0) a.split_units = can_split ? g_force_split : 0;
+    if (force_split >= 0) a.split_units = can_split ? force_split : 0;
     a.ks_log2 = 0;
     if (!a.split_units)
         while (a.ks_log2 < 2 && int64_t(a.n_tiles) * ((a.n_blocks + (nw >> a.ks_log2) - 1) / (nw >> a.ks_log2)) <= slots / 2)
             ++a.ks_log2;
-    if (g_force_ks >= 0) a.ks_log2 = g_force_ks;
+    if (force_ks >= 0) a.ks_log2 = force_ks;
     const int fw = nw >> a.ks_log2;
     a.n_groups = (a.n_blocks + fw - 1) / fw;
     const int64_t units = int64_t(a.n_tiles) * a.n_groups;
@@ -857,8 +883,8 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
         wgs = int64_t((a.n_tiles + 7) / 8) * 8 * a.n_groups;   // one per unit of the largest set, in every set
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const hipError_t e = nw == 16 ? launch_any<16, 8>(a, wgs, st, vec, layout, dtype)
-                                  : launch_any<8, 4>(a, wgs, st, vec, layout, dtype);
+    const hipError_t e = nw == 16 ? launch_any<16, 8>(a, wgs, st, vec, layout, dtype, h->device)
+                                  : launch_any<8, 4>(a, wgs, st, vec, layout, dtype, h->device);
     if (e != hipSuccess) {
         set_error(std::string("pconv_conv2d (tiled kernel): ") + hipGetErrorName(e));
         return PCONV_HIP_ERROR;

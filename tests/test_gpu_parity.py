@@ -23,6 +23,7 @@ def _reset_policy():
     yield
     P.pconv_set_kernel_policy(0)
     P.pconv_debug_set_tiling(0, -1, -1)
+    P.pconv_debug_set_spin_limit(0)
 
 
 def check_full(spec, L, x, dtype, layout="nchw", stride=1, relu=False, use_bias=True, policy=0, what=""):
@@ -90,9 +91,10 @@ def test_config3_vgg_chained_with_maxpool_batch2():
     assert tuple(cur.shape) == (2, 512, 7, 7)
 
 
-@pytest.mark.parametrize("idx", [1, 5, 9, 12])
+@pytest.mark.parametrize("idx", [0, 2, 4, 7, 10, 1, 5, 9, 12])
 def test_config3_vgg_batch32_sampled(idx):
-    """Bench launch configuration (batch 32) on sampled outputs the oracle computes one by one."""
+    """Bench launch configuration (batch 32) on sampled outputs the oracle computes one by one:
+    every layer shape that the benchmark runs through pconv_conv2d."""
     spec = config_layers(3, batch=32)[idx]
     L = make_layer(spec, base_seed(3) + 100 * idx); x = make_input(spec, base_seed(3) + 100 * idx)
     say(f"[case] {spec.name} N=32 sampled")
@@ -104,7 +106,7 @@ def test_config3_vgg_batch32_sampled(idx):
     h.free()
 
 
-@pytest.mark.parametrize("idx", [1, 9])
+@pytest.mark.parametrize("idx", [1, 3, 6, 9])
 def test_config3_vgg_batch32_fused_pool_sampled(idx):
     """The fused convolution + max-pool launches of the benchmark (batch 32) on sampled pooled
     outputs: the oracle computes the four convolution outputs under each of them one by one."""
@@ -244,6 +246,75 @@ def test_tiled_kernel_every_workgroup_shape_and_channel_split(waves, ks_log2, sp
             L = make_layer(spec, 2000 + j); x = make_input(spec, 2000 + j, layout)
             check_full(spec, L, x, dtype, layout, 1, relu=bool(j & 1), policy=2,
                        what=f"tiling{j}_w{waves}_ks{ks_log2}_split{split_units}")
+
+
+# Layers whose pieces walk more than 64 chunks of input channels (the bounds of the chunks sit one
+# per lane and are re-read every 64 chunks): c_in above 512 with 8-channel chunks, above 256 with
+# the 8-wave shape's 4-channel chunks.  Small images keep the oracle cheap.
+@pytest.mark.parametrize("waves,c_in,split_units", [(16, 520, 0), (16, 520, 1), (16, 1030, 0), (16, 1030, 1),
+                                                     (8, 300, 0), (8, 300, 1)])
+def test_more_than_64_chunks_of_input_channels(waves, c_in, split_units):
+    P.pconv_debug_set_tiling(waves, 0, split_units)
+    for j, (n, co, h, w) in enumerate([(1, 24, 8, 8), (2, 70, 5, 12)]):
+        spec = LayerSpec(f"deep{j}", n, c_in, co, h, w, num_patterns=8, pattern_dist="uniform",
+                         keep_div=3.0, count_dist="bernoulli")
+        L = make_layer(spec, 4000 + j); x = make_input(spec, 4000 + j)
+        check_full(spec, L, x, "f32", "nchw", 1, relu=bool(j), policy=2,
+                   what=f"deep{j}_cin{c_in}_w{waves}_split{split_units}")
+
+
+# Units shared between workgroups on layers of several tiles, also where the image width is no
+# multiple of 4: there the last patch of a row overlaps its neighbour, and when the two lie in
+# different tiles the library must not let their workgroups pass partial sums through the
+# columns they share (it then keeps whole units).
+@pytest.mark.parametrize("split_units", [-1, 1])
+@pytest.mark.parametrize("shape", [(4, 256, 64, 18, 18), (32, 256, 256, 10, 10), (3, 96, 64, 20, 24),
+                                   (6, 72, 128, 14, 14), (2, 64, 64, 30, 26)])
+def test_shared_units_on_several_tiles(shape, split_units):
+    n, ci, co, h, w = shape
+    P.pconv_debug_set_tiling(0, -1, split_units)
+    spec = LayerSpec("multitile", n, ci, co, h, w)
+    L = make_layer(spec, 5000 + h); x = make_input(spec, 5000 + h)
+    check_full(spec, L, x, "f32", "nchw", 1, relu=True, policy=2, what=f"multitile{shape}_split{split_units}")
+
+
+def test_four_scp_table():
+    """A table of the paper's four Sparse Convolution Patterns alone (the 4-pattern row of the
+    pattern-count experiment)."""
+    for j, (n, ci, co, h, w) in enumerate([(2, 40, 70, 14, 14), (1, 64, 64, 28, 28)]):
+        spec = LayerSpec(f"scp4_{j}", n, ci, co, h, w, num_patterns=4, pattern_dist="uniform")
+        L = make_layer(spec, 6000 + j); x = make_input(spec, 6000 + j)
+        assert len(L["table"]) == 4
+        for policy in POLICIES:
+            check_full(spec, L, x, "f32", relu=True, policy=policy, what=f"scp4_{j}")
+
+
+def test_expired_wait_is_reported_by_the_next_call():
+    """Error path, forced from the host: with a spin limit of 1 every bounded wait inside the tiled
+    kernel gives up at once.  The kernels still run to their end; the handle reports the failure
+    on the next call (which launches nothing) and works again afterwards."""
+    import torch
+    spec = config_layers(2)[0]                       # shared units: both kinds of wait are used
+    L = make_layer(spec, base_seed(2)); x = make_input(spec, base_seed(2))
+    h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
+    xd = to_device(x, "f32"); b = torch.from_numpy(L["bias"]).cuda()
+    good = P.conv2d(h, xd, b, relu=True).clone()
+    torch.cuda.synchronize()
+    P.pconv_get_async_error(h)                       # nothing to report
+    say("[case] spin limit 1")
+    P.pconv_debug_set_spin_limit(1)
+    P.conv2d(h, xd, b, relu=True)
+    torch.cuda.synchronize()
+    P.pconv_debug_set_spin_limit(0)
+    with pytest.raises(P.PconvError) as e:
+        P.conv2d(h, xd, b, relu=True)
+    assert e.value.status == P.HIP_ERROR and "bounded wait" in str(e.value)
+    P.pconv_get_async_error(h)                       # reported once
+    y = P.conv2d(h, xd, b, relu=True)
+    torch.cuda.synchronize()
+    assert torch.equal(y, good)
+    P.pconv_get_async_error(h)
+    h.free()
 
 
 @pytest.mark.parametrize("policy", POLICIES)
