@@ -100,6 +100,22 @@ int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const fl
                  pconv_layout layout, pconv_dtype act_dtype, int fuse_relu, void *hip_stream);
 
 /*
+ * pconv_conv2d_static - pconv_conv2d for callers that must not cause, or depend on, any device
+ * allocation of the library's: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels, same results.  The one difference: the
+ * hand-over words that workgroups use when they share tiles come from a static array in the
+ * library's code object (1024 words = 4 KiB per device, held until the process ends) instead of
+ * from the handle; a small fill kernel clears them on hip_stream ahead of the convolution.  The
+ * call itself allocates and frees nothing.  All calls on one device share that array: calls of
+ * this entry point that overlap on one device (different streams) race and must be serialised by
+ * the caller.  Errors: as pconv_conv2d; PCONV_UNSUPPORTED if a launch would need more hand-over
+ * words than the array has; PCONV_HIP_ERROR if the array's address cannot be obtained.
+ */
+int pconv_conv2d_static(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
+                        int n, int h_in, int w_in, int stride, int pad,
+                        pconv_layout layout, pconv_dtype act_dtype, int fuse_relu, void *hip_stream);
+
+/*
  * pconv_get_async_error - PCONV_HIP_ERROR (once, with a message) if a kernel launched on this
  * handle gave up one of its bounded waits since the last report, else PCONV_OK.  Touches no
  * device; meaningful after the stream(s) of the calls in question have been synchronised.

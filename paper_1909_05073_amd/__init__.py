@@ -58,6 +58,8 @@ def lib():
     L.pconv_debug_pack_host.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, C.POINTER(vp)]
     L.pconv_conv2d.restype = ip
     L.pconv_conv2d.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, ip, ip, vp]
+    L.pconv_conv2d_static.restype = ip
+    L.pconv_conv2d_static.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, ip, ip, vp]
     L.pconv_conv2d_pool2x2.restype = ip
     L.pconv_conv2d_pool2x2.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, ip, vp]
     L.pconv_free.restype = None
@@ -86,7 +88,7 @@ def lib():
     return L
 
 
-EXPORTED_SYMBOLS = ["pconv_pack", "pconv_conv2d", "pconv_conv2d_pool2x2", "pconv_free", "pconv_maxpool2x2",
+EXPORTED_SYMBOLS = ["pconv_pack", "pconv_conv2d", "pconv_conv2d_static", "pconv_conv2d_pool2x2", "pconv_free", "pconv_maxpool2x2",
                     "pconv_get_info", "pconv_debug_export", "pconv_debug_export_blocks", "pconv_debug_pack_host",
                     "pconv_debug_unpack",
                     "pconv_set_kernel_policy", "pconv_debug_set_tiling", "pconv_debug_set_spin_limit",
@@ -150,6 +152,15 @@ def pconv_conv2d(handle: Handle, x_ptr: int, y_ptr: int, bias_ptr, n: int, h_in:
     _check(lib().pconv_conv2d(handle.ptr, x_ptr, y_ptr, bias_ptr or None, n, h_in, w_in, stride, pad,
                               _LAYOUT[layout], _DTYPE[act_dtype], int(bool(fuse_relu)),
                               stream or None))
+
+
+def pconv_conv2d_static(handle: Handle, x_ptr: int, y_ptr: int, bias_ptr, n: int, h_in: int, w_in: int,
+                        stride: int = 1, pad: int = 1, layout=NCHW, act_dtype=F32, fuse_relu: bool = False,
+                        stream: int = 0):
+    """Raw-pointer call, one to one with the C entry point."""
+    _check(lib().pconv_conv2d_static(handle.ptr, x_ptr, y_ptr, bias_ptr or None, n, h_in, w_in, stride, pad,
+                                     _LAYOUT[layout], _DTYPE[act_dtype], int(bool(fuse_relu)),
+                                     stream or None))
 
 
 def pconv_conv2d_pool2x2(handle: Handle, x_ptr: int, y_ptr: int, bias_ptr, n: int, h_in: int, w_in: int,

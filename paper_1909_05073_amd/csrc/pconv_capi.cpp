@@ -194,7 +194,7 @@ int pconv_get_info(const pconv_handle *h, pconv_info *info)
 
 static int conv2d_impl(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
                        int n, int h_in, int w_in, int stride, int pad, pconv_layout layout,
-                       pconv_dtype act_dtype, int fuse_relu, void *hip_stream)
+                       pconv_dtype act_dtype, int fuse_relu, void *hip_stream, bool static_scratch)
 {
     if (!h || !x_dev || !y_dev) { set_error("pconv_conv2d: null pointer argument"); return PCONV_INVALID_ARG; }
     if (x_dev == y_dev) { set_error("pconv_conv2d: y_dev must not alias x_dev"); return PCONV_INVALID_ARG; }
@@ -217,7 +217,7 @@ static int conv2d_impl(const pconv_handle *h, const void *x_dev, void *y_dev, co
     if (policy == 2 && !can_tile) { set_error("pconv_conv2d: register-tiled kernel not available for this call"); return PCONV_UNSUPPORTED; }
     if (can_tile && (policy == 2 || (policy == 0 && tiled_preferred(h_in, w_in, stride))))
         return launch_conv_tiled(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, int(layout),
-                                 int(act_dtype), fuse_relu ? 1 : 0, 0, hip_stream);
+                                 int(act_dtype), fuse_relu ? 1 : 0, 0, hip_stream, static_scratch);
     return launch_conv_generic(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, int(layout),
                                int(act_dtype), fuse_relu ? 1 : 0, hip_stream);
 }
@@ -227,7 +227,15 @@ int pconv_conv2d(const pconv_handle *h, const void *x_dev, void *y_dev, const fl
                  pconv_dtype act_dtype, int fuse_relu, void *hip_stream)
 {
     return conv2d_impl(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, pad, layout, act_dtype, fuse_relu,
-                       hip_stream);
+                       hip_stream, false);
+}
+
+int pconv_conv2d_static(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,
+                        int n, int h_in, int w_in, int stride, int pad, pconv_layout layout,
+                        pconv_dtype act_dtype, int fuse_relu, void *hip_stream)
+{
+    return conv2d_impl(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, pad, layout, act_dtype, fuse_relu,
+                       hip_stream, true);
 }
 
 int pconv_conv2d_pool2x2(const pconv_handle *h, const void *x_dev, void *y_dev, const float *bias_dev,

@@ -84,8 +84,10 @@ void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int 
 // Kernel launchers (pconv_kernels.hip, pconv_tiled.hip).  All return a pconv_status.
 int launch_conv_generic(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
                         int hin, int win, int stride, int layout, int dtype, int relu, void *stream);
+// static_scratch: take the hand-over words from the code object's static array instead of the handle.
 int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
-                      int hin, int win, int stride, int layout, int dtype, int relu, int pool, void *stream);
+                      int hin, int win, int stride, int layout, int dtype, int relu, int pool, void *stream,
+                      bool static_scratch = false);
 // whether the tiled kernel can write the 2x2 max-pooled output directly (pool = 1)
 bool tiled_pool_supported(const pconv_handle *h, int n, int hin, int win, int layout, int dtype);
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype);

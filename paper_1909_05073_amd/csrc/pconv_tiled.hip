@@ -28,6 +28,11 @@
 #include "pconv_internal.h"
 #include "pconv_tiled_codes.h"
 
+// Hand-over words for callers that cannot let the library allocate (pconv_conv2d_static): one row
+// of kFlagWords words per device, in the code object itself.  Host code never uses this name as an
+// address; it asks the runtime for the array's device address once per device (static_flags()).
+static __device__ __align__(256) uint32_t scratch[pconv::kFlagWords];
+
 namespace pconv {
 
 namespace {
@@ -818,8 +823,40 @@ bool tiled_pool_supported(const pconv_handle *h, int n, int hin, int win, int la
            win >= 4 && win % 2 == 0 && hin >= 2 && int64_t(n) * h->c_in * hin * win * 4 < (int64_t(1) << 31);
 }
 
+namespace {
+
+__global__ void fill_words_kernel(uint32_t *p, int count, uint32_t value)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = value;
+}
+
+// Device address of `scratch` on the handle's device (which is the current one), looked up on the
+// first call per device and kept; nullptr (message set) if the runtime refuses.
+uint32_t *static_flags(int dev)
+{
+    static std::atomic<uint32_t *> ptrs[64];
+    if (dev < 0 || dev >= 64) { set_error("pconv_conv2d_static: device index out of range"); return nullptr; }
+    uint32_t *p = ptrs[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    void *sym = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !sym) {
+        set_error(std::string("pconv_conv2d_static: hipGetSymbolAddress: ") + hipGetErrorName(e));
+        return nullptr;
+    }
+    p = static_cast<uint32_t *>(sym);
+    ptrs[dev].store(p, std::memory_order_release);   // (every thread gets the same address)
+    return p;
+}
+
+std::atomic<uint32_t> g_static_calls{0};             // epochs of the calls that use `scratch`
+
+}  // namespace
+
 int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
-                      int hin, int win, int stride, int layout, int dtype, int relu, int pool, void *stream)
+                      int hin, int win, int stride, int layout, int dtype, int relu, int pool, void *stream,
+                      bool static_scratch)
 {
     TiledArgs a;
     a.sub2 = stride == 2;
@@ -876,9 +913,23 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
         // one workgroup per slot, but no fewer than two chunks each
         const int64_t iters = units * a.n_chunks;
         wgs = std::min<int64_t>(std::min<int>(slots, kFlagWords), std::max<int64_t>(8, iters / 2));
-        const uint32_t call = h->calls.fetch_add(1u);
-        a.flags = h->d_flags + size_t(call % kFlagSlots) * kFlagWords;
-        a.epoch = call + 1u ? call + 1u : 1u;
+        if (static_scratch) {
+            // the one row of the device's static array, cleared by a small kernel ahead of the
+            // convolution on the same stream (calls that overlap on one device would race here)
+            if (wgs > kFlagWords) { set_error("pconv_conv2d_static: more workgroups than hand-over words"); return PCONV_UNSUPPORTED; }
+            uint32_t *row = static_flags(h->device);
+            if (!row) return PCONV_HIP_ERROR;
+            hipLaunchKernelGGL(fill_words_kernel, dim3((kFlagWords + 255) / 256), dim3(256), 0,
+                               static_cast<hipStream_t>(stream), row, kFlagWords, 0u);
+            if (hipGetLastError() != hipSuccess) { set_error("pconv_conv2d_static: clearing the hand-over words failed"); return PCONV_HIP_ERROR; }
+            const uint32_t call = g_static_calls.fetch_add(1u);
+            a.flags = row;
+            a.epoch = call + 1u ? call + 1u : 1u;
+        } else {
+            const uint32_t call = h->calls.fetch_add(1u);
+            a.flags = h->d_flags + size_t(call % kFlagSlots) * kFlagWords;
+            a.epoch = call + 1u ? call + 1u : 1u;
+        }
     } else {
         wgs = int64_t((a.n_tiles + 7) / 8) * 8 * a.n_groups;   // one per unit of the largest set, in every set
     }
