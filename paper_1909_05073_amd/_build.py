@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpconv.so")
-SOURCES = ["pconv_capi.cpp", "pconv_pack.cpp", "pconv_kernels.hip", "pconv_tiled.hip"]
+SOURCES = ["pconv_capi.cpp", "pconv_pack.cpp", "pconv_kernels.hip", "pconv_tiled.hip", "pconv_mfma.hip"]
 
 # packed-FP32 instructions are switched off for every device compile of this project
 HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -15,10 +15,10 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
              "-Wall", "-Wno-unused-command-line-argument"]
 
 
-# The tiled kernel dispatches on wave-uniform record codes with a large switch.  By default the
-# AMDGPU backend structurizes uniform control flow as well, which turns that switch into a long
-# chain of guarded blocks with register copies at every join; this option keeps uniform regions
-# as the binary compare tree they are.
+# The tiled kernel is full of wave-uniform branches (which piece of work, which staging unit, whether
+# a wave stages at all).  By default the AMDGPU backend structurizes uniform control flow as well,
+# with guarded blocks and register copies at every join; this option leaves uniform regions as the
+# plain branches they are.
 EXTRA_FLAGS = {"pconv_tiled.hip": ["-mllvm", "-structurizecfg-skip-uniform-regions"]}
 
 

@@ -42,7 +42,7 @@ int upload(T *&dst, const T *src, size_t count, int64_t &bytes)
 void release_device(pconv_handle *h)
 {
     void *ptrs[] = {h->d_perm, h->d_row_ptr, h->d_kern, h->d_val_ptr, h->d_vals,
-                    h->d_slot_filter, h->d_chan_ptr, h->d_meta, h->d_w4, h->d_flags};
+                    h->d_slot_filter, h->d_chan_ptr, h->d_meta, h->d_w4, h->d_flags, h->d_wdense, h->d_wnz};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (h->h_err) (void)hipHostFree(h->h_err);
@@ -72,7 +72,7 @@ const char *pconv_last_error(void) { return get_error(); }
 
 int pconv_set_kernel_policy(int policy)
 {
-    if (policy < 0 || policy > 2) { set_error("pconv_set_kernel_policy: policy must be 0, 1 or 2"); return PCONV_INVALID_ARG; }
+    if (policy < 0 || policy > 3) { set_error("pconv_set_kernel_policy: policy must be 0, 1, 2 or 3"); return PCONV_INVALID_ARG; }
     g_policy.store(policy);
     return PCONV_OK;
 }
@@ -135,6 +135,12 @@ static int pack_impl(const float *w_dense, const uint8_t *pattern_id, const uint
         if (rc == PCONV_OK) rc = upload(h->d_chan_ptr, h->tiled.chan_ptr.data(), h->tiled.chan_ptr.size(), h->device_bytes);
         if (rc == PCONV_OK) rc = upload(h->d_meta, h->tiled.meta.data(), h->tiled.meta.size(), h->device_bytes);
         if (rc == PCONV_OK) rc = upload(h->d_w4, h->tiled.w4.data(), h->tiled.w4.size(), h->device_bytes);
+        if (rc == PCONV_OK && weight_dtype == PCONV_BF16) {
+            std::vector<uint16_t> wd; std::vector<uint32_t> nz;
+            build_dense_taps(h->canon, table, c_out, c_in, wd, nz);
+            rc = upload(h->d_wdense, wd.data(), wd.size(), h->device_bytes);
+            if (rc == PCONV_OK) rc = upload(h->d_wnz, nz.data(), nz.size(), h->device_bytes);
+        }
         if (rc == PCONV_OK) {
             const std::vector<uint32_t> zeros(size_t(kFlagSlots) * kFlagWords, 0u);
             rc = upload(h->d_flags, zeros.data(), zeros.size(), h->device_bytes);
@@ -213,6 +219,10 @@ static int conv2d_impl(const pconv_handle *h, const void *x_dev, void *y_dev, co
     }
     if (const int rc = take_async_error(h, "pconv_conv2d")) return rc;
     const int policy = g_policy.load();
+    const bool can_mfma = mfma_supported(h, int(act_dtype));
+    if (policy == 3 && !can_mfma) { set_error("pconv_conv2d: the matrix-core kernel serves bf16 handles only"); return PCONV_UNSUPPORTED; }
+    if (can_mfma && (policy == 3 || (policy == 0 && mfma_preferred(h))))
+        return launch_conv_mfma(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, int(layout), fuse_relu ? 1 : 0, hip_stream);
     const bool can_tile = tiled_supported(h, n, h_in, w_in, stride, int(layout), int(act_dtype));
     if (policy == 2 && !can_tile) { set_error("pconv_conv2d: register-tiled kernel not available for this call"); return PCONV_UNSUPPORTED; }
     if (can_tile && (policy == 2 || (policy == 0 && tiled_preferred(h_in, w_in, stride))))

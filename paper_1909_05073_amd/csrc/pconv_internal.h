@@ -60,6 +60,13 @@ struct pconv_handle {
     uint32_t *d_chan_ptr = nullptr;
     uint32_t *d_meta = nullptr;
     float    *d_w4 = nullptr;
+    // device copies (matrix-core kernel, bf16 handles only): the masked weights as nine dense
+    // [filter][channel] matrices, tap-major, in blocks of 16 channels: [9][cb16][fpad][16] bf16, fpad
+    // = c_out rounded up to 32, cb16 = c_in rounded up to 32, in sixteens; and per (block of 32
+    // channels, block of 32 filters) a word whose bit 2 * tap + half says whether that
+    // (tap, 16 channels, 32 filters) block holds any kept weight
+    uint16_t *d_wdense = nullptr;
+    uint32_t *d_wnz = nullptr;
     // Hand-over words of the tiled kernel: workgroups that share a unit of work signal each other
     // through kFlagWords words; every call takes the next of kFlagSlots such rows and a fresh
     // value, so calls that overlap on different streams do not see each other's signals.
@@ -99,6 +106,14 @@ bool tiled_preferred(int hin, int win, int stride);
 void set_tiled_tuning(int waves, int ks_log2, int split_units);
 // Test override of the iteration limit of the kernels' bounded waits (<= 0 restores the default).
 void set_tiled_spin_limit(int limit);
+// bf16 layers on the matrix cores (pconv_mfma.hip)
+bool mfma_supported(const pconv_handle *h, int dtype);
+bool mfma_preferred(const pconv_handle *h);
+int launch_conv_mfma(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
+                     int hin, int win, int stride, int layout, int relu, void *stream);
+// masked weights of a bf16 handle in the matrix-core kernel's layout (see pconv_handle::d_wdense)
+void build_dense_taps(const Canonical &cn, const uint16_t *table, int c_out, int c_in,
+                      std::vector<uint16_t> &wd, std::vector<uint32_t> &nz);
 int launch_maxpool2x2(const void *x, void *y, int n, int c, int h, int w, int layout, int dtype,
                       void *stream);
 

@@ -254,4 +254,26 @@ void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int 
     for (int j = 0; j < 4; ++j) out.w4.push_back(0.0f);
 }
 
+// ---- dense per-tap matrices of the matrix-core kernel -----------------------------------
+void build_dense_taps(const Canonical &cn, const uint16_t *table, int c_out, int c_in,
+                      std::vector<uint16_t> &wd, std::vector<uint32_t> &nz)
+{
+    const int fpad = (c_out + 31) / 32 * 32, cb32 = (c_in + 31) / 32, cb16 = cb32 * 2;
+    wd.assign(size_t(9) * cb16 * fpad * 16, 0);
+    nz.assign(size_t(cb32) * (fpad / 32), 0u);
+    for (int i = 0; i < c_out; ++i) {
+        const int f = cn.perm[i];
+        for (uint32_t k = cn.row_ptr[i]; k < cn.row_ptr[i + 1]; ++k) {
+            const int c = cn.cin[k];
+            const unsigned mask = table[cn.pat[k]];
+            uint32_t v = cn.val_ptr[k];
+            for (int t = 0; t < 9; ++t)
+                if (mask & (1u << t)) {
+                    wd[((size_t(t) * cb16 + c / 16) * fpad + f) * 16 + c % 16] = uint16_t(cn.vals_bits[v++] >> 16);
+                    nz[size_t(c / 32) * (fpad / 32) + f / 32] |= 1u << (2 * t + (c / 16) % 2);
+                }
+        }
+    }
+}
+
 }  // namespace pconv

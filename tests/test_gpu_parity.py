@@ -15,7 +15,8 @@ from gpu_util import (assert_close, gather_points, gpu_conv, oracle_full, sample
 
 pytestmark = pytest.mark.gpu
 
-POLICIES = [1, 0]          # 1 = generic gather kernel, 0 = automatic (register-tiled where possible)
+POLICIES = [1, 0]          # 1 = generic gather kernel, 0 = automatic (register-tiled / matrix-core where possible)
+# (2 = register-tiled vector kernel required, 3 = matrix-core kernel required: bf16 handles only)
 
 
 @pytest.fixture(autouse=True)
@@ -161,9 +162,13 @@ def test_input_just_below_and_above_2_gib(w):
     hd.free()
 
 
-def test_config4_resnet_bf16():
-    """All sixteen ResNet-50 3x3 layers (stride 2 included), bf16 in/out, fp32 accumulate."""
+@pytest.mark.parametrize("policy", [0, 2])
+def test_config4_resnet_bf16(policy):
+    """All sixteen ResNet-50 3x3 layers (stride 2 included), bf16 in/out, fp32 accumulate: as the
+    library chooses (the matrix-core kernel at this density) and on the vector kernel."""
     seen = set()
+    P.pconv_set_kernel_policy(policy)
+    shares = []
     for i, spec in enumerate(config_layers(4, batch=32)):
         key = (spec.c_in, spec.h, spec.stride)
         L = make_layer(spec, base_seed(4) + i); x = make_input(spec, base_seed(4) + i)
@@ -172,11 +177,17 @@ def test_config4_resnet_bf16():
         wt = oracle.masked_weights(L["w"], L["pattern_id"], L["conn"], L["table"], "bf16")
         pts = sample_points(np.random.default_rng(i), 32, spec.c_out, spec.h_out, spec.w_out, 8000)
         yr, sr = oracle.conv2d_points(x, wt, pts, L["bias"], stride=spec.stride, relu=True)
-        assert_close(gather_points(y, pts, "nchw"), yr, sr, "bf16", spec.name)
+        yg = gather_points(y, pts, "nchw")
+        assert_close(yg, yr, sr, "bf16", spec.name)
+        # secondary figure: share of the sampled outputs within 2e-2 of the oracle value itself
+        big = np.abs(yr) > 0
+        shares.append(float(np.mean(np.abs(yg - yr)[big] <= 2e-2 * np.abs(yr[big]))))
         if key not in seen:                      # full-output check at batch 2 once per shape
             seen.add(key)
-            check_full(spec, L, x[:2], "bf16", stride=spec.stride, relu=True, what=spec.name + "_n2")
+            check_full(spec, L, x[:2], "bf16", stride=spec.stride, relu=True, policy=policy, what=spec.name + "_n2")
         h.free()
+    say(f"[info] config 4, policy {policy}: share of non-zero sampled outputs with |err| <= 2e-2*|y|: "
+        f"min {min(shares):.4f} mean {np.mean(shares):.4f} over {len(shares)} layers")
 
 
 def test_config5_stress_imbalanced():
@@ -202,11 +213,13 @@ EDGE_SHAPES = [  # (n, c_in, c_out, h, w)
 ]
 
 
-@pytest.mark.parametrize("policy", POLICIES + [2])      # 2 = register-tiled kernel for every call (small stride-2 layers too)
+@pytest.mark.parametrize("policy", POLICIES + [2, 3])   # 2 = register-tiled kernel for every call (small stride-2 layers too)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("layout", ["nchw", "nhwc"])
 @pytest.mark.parametrize("stride", [1, 2])
 def test_ragged_shapes_layouts_strides(policy, dtype, layout, stride):
+    if policy == 3 and dtype == "f32":
+        pytest.skip("the matrix-core kernel serves bf16 only (see test_matrix_core_kernel_rejects_fp32)")
     for j, (n, ci, co, h, w) in enumerate(EDGE_SHAPES):
         spec = LayerSpec(f"edge{j}", n, ci, co, h, w, stride=stride, dtype=dtype, num_patterns=12,
                          pattern_dist="uniform", keep_div=2.0, count_dist="bernoulli")
@@ -372,6 +385,52 @@ def test_fused_maxpool_equals_conv_then_pool(waves, ks_log2):
             torch.cuda.synchronize()
             assert torch.equal(y, y2), f"pool{j}: fused and separate results differ"
             hd.free()
+
+
+MFMA_SHAPES = [  # (n, c_in, c_out, h, w, stride): several channel blocks, ragged filter blocks, tiles of every kind
+    (2, 64, 64, 56, 56, 1), (3, 40, 70, 28, 28, 1), (5, 96, 33, 14, 14, 1), (9, 130, 64, 7, 7, 1),
+    (2, 64, 96, 56, 56, 2), (3, 48, 40, 29, 31, 2), (1, 16, 8, 3, 300, 1), (1, 8, 160, 40, 9, 1),
+]
+
+
+@pytest.mark.parametrize("layout", ["nchw", "nhwc"])
+def test_matrix_core_kernel_shapes(layout):
+    """The bf16 matrix-core kernel on every kind of tile it builds (rows of one image, whole images,
+    several images, split rows), both strides, channel and filter counts off the block sizes."""
+    for j, (n, ci, co, h, w, stride) in enumerate(MFMA_SHAPES):
+        spec = LayerSpec(f"mfma{j}", n, ci, co, h, w, stride=stride, dtype="bf16", keep_div=2.5)
+        L = make_layer(spec, 7000 + j); x = make_input(spec, 7000 + j, layout)
+        check_full(spec, L, x, "bf16", layout, stride, relu=bool(j & 1), use_bias=not (j & 2), policy=3,
+                   what=f"mfma{j}_{layout}")
+
+
+def test_matrix_core_kernel_skips_empty_weight_blocks():
+    """Connectivity so sparse that whole (tap, 16 channels, 32 filters) blocks hold no weight: the
+    kernel skips them; and a layer with nothing kept at all."""
+    rng = np.random.default_rng(11)
+    f, c = 70, 100
+    spec = LayerSpec("mfma_sparse", 2, c, f, 12, 12, dtype="bf16", num_patterns=4, pattern_dist="uniform")
+    L = make_layer(spec, 7100)
+    L["conn"][:] = 0
+    L["conn"][rng.integers(0, f, 40), rng.integers(0, c, 40)] = 1
+    L["conn"][:, 32:64] = 0                          # a whole block of channels unused
+    x = make_input(spec, 7100)
+    check_full(spec, L, x, "bf16", relu=False, policy=3, what="mfma sparse")
+    L["conn"][:] = 0
+    check_full(spec, L, x, "bf16", relu=True, policy=3, what="mfma empty")
+
+
+def test_matrix_core_kernel_rejects_fp32():
+    import torch
+    spec = config_layers(1)[0]
+    L = make_layer(spec, base_seed(1))
+    h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], L["table"], "f32")
+    x = torch.zeros(1, 16, 16, 16, device="cuda"); y = torch.zeros_like(x)
+    P.pconv_set_kernel_policy(3)
+    with pytest.raises(P.PconvError) as e:
+        P.pconv_conv2d(h, x.data_ptr(), y.data_ptr(), 0, 1, 16, 16)
+    assert e.value.status == P.UNSUPPORTED
+    h.free()
 
 
 def test_fused_maxpool_rejects_what_it_cannot_do():
