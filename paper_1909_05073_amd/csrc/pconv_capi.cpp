@@ -219,8 +219,8 @@ static int conv2d_impl(const pconv_handle *h, const void *x_dev, void *y_dev, co
     }
     if (const int rc = take_async_error(h, "pconv_conv2d")) return rc;
     const int policy = g_policy.load();
-    const bool can_mfma = mfma_supported(h, int(act_dtype));
-    if (policy == 3 && !can_mfma) { set_error("pconv_conv2d: the matrix-core kernel serves bf16 handles only"); return PCONV_UNSUPPORTED; }
+    const bool can_mfma = mfma_supported(h, int(act_dtype), n, h_in, w_in);
+    if (policy == 3 && !can_mfma) { set_error("pconv_conv2d: the matrix-core kernel serves bf16 handles with inputs below 2 GiB only"); return PCONV_UNSUPPORTED; }
     if (can_mfma && (policy == 3 || (policy == 0 && mfma_preferred(h))))
         return launch_conv_mfma(h, x_dev, y_dev, bias_dev, n, h_in, w_in, stride, int(layout), fuse_relu ? 1 : 0, hip_stream);
     const bool can_tile = tiled_supported(h, n, h_in, w_in, stride, int(layout), int(act_dtype));

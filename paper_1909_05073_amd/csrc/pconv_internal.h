@@ -107,7 +107,7 @@ void set_tiled_tuning(int waves, int ks_log2, int split_units);
 // Test override of the iteration limit of the kernels' bounded waits (<= 0 restores the default).
 void set_tiled_spin_limit(int limit);
 // bf16 layers on the matrix cores (pconv_mfma.hip)
-bool mfma_supported(const pconv_handle *h, int dtype);
+bool mfma_supported(const pconv_handle *h, int dtype, int n, int hin, int win);
 bool mfma_preferred(const pconv_handle *h);
 int launch_conv_mfma(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
                      int hin, int win, int stride, int layout, int relu, void *stream);
