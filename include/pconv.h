@@ -138,6 +138,15 @@ int pconv_conv2d_pool2x2(const pconv_handle *h, const void *x_dev, void *y_dev, 
                          int n, int h_in, int w_in, pconv_layout layout, pconv_dtype act_dtype,
                          int fuse_relu, void *hip_stream);
 
+/*
+ * pconv_pool2x2_fusion - what pconv_conv2d_pool2x2 would do with this call, without launching
+ * anything: 0 = not supported (use pconv_conv2d + pconv_maxpool2x2), 1 = supported, but the layer has
+ * so few tiles that pconv_conv2d would let workgroups share them, which the fused call cannot (the
+ * two separate calls are expected to be faster), 2 = supported and recommended.  Negative = error.
+ */
+int pconv_pool2x2_fusion(const pconv_handle *h, int n, int h_in, int w_in, pconv_layout layout,
+                         pconv_dtype act_dtype);
+
 /* pconv_free - releases the handle's host and device memory.  NULL is allowed. */
 void pconv_free(pconv_handle *h);
 
@@ -201,9 +210,13 @@ int pconv_debug_export_blocks(const pconv_handle *h, int32_t *slot_filter, uint3
  * from the DEVICE copy of the packed data (zeros where nothing is stored). */
 int pconv_debug_unpack(const pconv_handle *h, float *w_dense_out);
 
-/* Kernel selection, for tests and benchmarks: 0 = automatic (default), 1 = always the
- * generic gather kernel, 2 = require the register-tiled kernel (PCONV_UNSUPPORTED if the
- * handle or the call cannot use it).  Process-wide. */
+/* Kernel selection, for tests and benchmarks: 0 = automatic (default: the register-tiled vector
+ * kernel; for bf16 handles that keep at least 1 weight in 20, the matrix-core kernel, which runs
+ * the nine taps of Eq. (1) as dense bf16 contractions over the masked weights with fp32
+ * accumulation; the gather kernel for what neither serves), 1 = always the generic gather kernel,
+ * 2 = require the register-tiled kernel, 3 = require the matrix-core kernel (bf16 handles, inputs
+ * below 2 GiB).  2 and 3 give PCONV_UNSUPPORTED if the handle or the call cannot use the kernel.
+ * Process-wide. */
 int pconv_set_kernel_policy(int policy);
 
 /* pconv_debug_set_tiling - for tests: pins launch choices the register-tiled kernel otherwise
@@ -220,6 +233,13 @@ int pconv_debug_set_tiling(int waves, int ks_log2, int split_units);
  * their outputs are invalid, and the handle reports the error as described at pconv_conv2d.
  * Process-wide. */
 int pconv_debug_set_spin_limit(int limit);
+
+/* pconv_debug_measure_fma_peak - for benchmarks: runs a kernel of nothing but independent fp32
+ * FMAs on vector-register operands (16 waves per compute unit) on the current device and reports
+ * the rate in TFLOP/s: the measured counterpart of the datasheet's fp32 vector peak for the
+ * instruction the convolution kernel is made of.  Synchronous; allocates and frees a scratch
+ * buffer of its own. */
+int pconv_debug_measure_fma_peak(double *tflops);
 
 const char *pconv_last_error(void);
 

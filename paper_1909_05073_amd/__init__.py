@@ -82,6 +82,10 @@ def lib():
     L.pconv_debug_set_spin_limit.argtypes = [ip]
     L.pconv_get_async_error.restype = ip
     L.pconv_get_async_error.argtypes = [vp]
+    L.pconv_pool2x2_fusion.restype = ip
+    L.pconv_pool2x2_fusion.argtypes = [vp, ip, ip, ip, ip, ip]
+    L.pconv_debug_measure_fma_peak.restype = ip
+    L.pconv_debug_measure_fma_peak.argtypes = [C.POINTER(C.c_double)]
     L.pconv_last_error.restype = C.c_char_p
     L.pconv_last_error.argtypes = []
     _lib = L
@@ -92,7 +96,8 @@ EXPORTED_SYMBOLS = ["pconv_pack", "pconv_conv2d", "pconv_conv2d_static", "pconv_
                     "pconv_get_info", "pconv_debug_export", "pconv_debug_export_blocks", "pconv_debug_pack_host",
                     "pconv_debug_unpack",
                     "pconv_set_kernel_policy", "pconv_debug_set_tiling", "pconv_debug_set_spin_limit",
-                    "pconv_get_async_error", "pconv_last_error"]
+                    "pconv_get_async_error", "pconv_pool2x2_fusion", "pconv_debug_measure_fma_peak",
+                    "pconv_last_error"]
 
 
 def _check(rc: int):
@@ -182,11 +187,26 @@ def pconv_maxpool2x2(x_ptr: int, y_ptr: int, n: int, c: int, h: int, w: int, lay
 
 
 def pconv_set_kernel_policy(policy: int):
+    """0 automatic, 1 generic gather kernel, 2 register-tiled vector kernel, 3 matrix-core kernel (bf16)."""
     _check(lib().pconv_set_kernel_policy(int(policy)))
 
 
 def pconv_debug_set_tiling(waves: int = 0, ks_log2: int = -1, split_units: int = -1):
     _check(lib().pconv_debug_set_tiling(int(waves), int(ks_log2), int(split_units)))
+
+
+def pconv_pool2x2_fusion(handle: Handle, n: int, h_in: int, w_in: int, layout=NCHW, act_dtype=F32) -> int:
+    """0 = the fused call is not supported, 1 = supported but not recommended, 2 = recommended."""
+    rc = lib().pconv_pool2x2_fusion(handle.ptr, n, h_in, w_in, _LAYOUT[layout], _DTYPE[act_dtype])
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def pconv_debug_measure_fma_peak() -> float:
+    out = C.c_double()
+    _check(lib().pconv_debug_measure_fma_peak(C.byref(out)))
+    return out.value
 
 
 def pconv_debug_set_spin_limit(limit: int = 0):

@@ -14,45 +14,70 @@ pins / clobbers the same registers):
     v[28 + 4*r + m]                 input rows r = 0..5 of the lane's patch, columns x0..x0+3 (m = 0..3)
     v[52 + r], v[58 + r]            the halo columns x0-1 and x0+4 of row r
     v[24:27]                        the record's four weights (same value in every lane)
-    v22, v23                        LDS addresses
+    v22 LDS address of the patch, v23 LDS address of the next record's weights
     s84 record index, s85 record word, s90 scratch, s[92:93] address of body 0, s[94:95] target
 Operands: %[recm] per-lane record words (lane j = record j), %[va] per-lane LDS byte address of
 the lane's patch in the staged buffer (a staged channel is nine 1 KiB blocks of one 16-byte
 quad per lane: the six rows, then the twelve halo values), %[wa] LDS byte address
-of this wave's weight block (SGPR; 16 bytes per record), %[first] %[cnt] the records to run
-(SGPRs; first <= cnt <= 32; nothing is done when they are equal).
+of this wave's weight block (SGPR; 16 bytes per record), %[first] the first record to run (SGPR),
+%[chmask] channels per chunk - 1 (immediate; 7 or 3).
+
+Record word: bits 0-2 the channel within its chunk, bit 3 set on the first record of a channel (the
+lane's 6x6 neighbourhood is then reloaded from LDS before the record runs), bits 9 and up the case
+(slot * codes + code) times the body stride, i.e. the byte offset of the record's body in the
+table.  The list ends with a record whose case is one past the last body: its "body" is the end of
+the loop, so the loop itself counts nothing.
 """
 import sys
 
 ACC, INP, WREG = 64, 28, 24
 STRIDE_LOG2 = 9
-CODE_MASKS = [0x03A, 0x09A, 0x0B8, 0x0B2, 0x01B, 0x036, 0x0D8, 0x1B0, 0x113, 0x074, 0x191, 0x05C,
-              0x007, 0x038, 0x1C0, 0x001, 0x002, 0x004, 0x008, 0x010, 0x020, 0x040, 0x080, 0x100]
+
+
+def code_masks():
+    """The sub-masks ("codes") that get an inner loop of their own; bit 3 * r + s = tap (r, s).  This
+    list is the one source of the code table: the packer's copy is generated from it.
+
+    Every 4-tap mask that contains the centre tap (the shape of a PCONV pattern: 56 masks) is one
+    code, so a kernel of any such pattern table is one record.  Other masks are split at pack time
+    into the largest codes they contain: the three kernel rows (a dense kernel is three records),
+    the 36 pairs of taps and the nine single taps make that possible for every mask."""
+    taps = range(9)
+    four = [m for m in range(512) if bin(m).count("1") == 4 and (m >> 4) & 1]
+    rows = [0x007, 0x038, 0x1C0]
+    pairs = [(1 << a) | (1 << b) for a in taps for b in taps if a < b]
+    singles = [1 << a for a in taps]
+    return four + rows + pairs + singles
+
+
+CODE_MASKS = code_masks()
+
 SLOTS = 4
 QUAD_BYTES = 64 * 16             # one 16-byte quad of every lane
 CHAN_BYTES = 9 * QUAD_BYTES      # one staged channel: 64 patches x 36 floats
 
 
-def fetch(lines):
-    """Start fetching record s84: weights from LDS, record word from lane s84."""
+def fetch(lines, uid):
+    """Fetch record s84 and go to its body: weights from LDS, record word from lane s84, the patch
+    reload in line when the record starts a new channel, then one computed jump."""
     lines += [
-        "s_lshl_b32 s90, s84, 4",
-        "s_add_u32 s90, s90, %[wa]",
-        "v_mov_b32 v23, s90",
         "ds_read_b128 v[%d:%d], v23" % (WREG, WREG + 3),
+        "v_add_u32 v23, 16, v23",
         "v_readlane_b32 s85, %[recm], s84",
         "s_nop 0",
-        "s_bitcmp1_b32 s85, 11",
+        "s_bitcmp1_b32 s85, 3",
+        "s_cbranch_scc0 GO_%s_%%=" % uid,
+        "s_and_b32 s90, s85, %[chmask]",
+        "s_mul_i32 s90, s90, %d" % CHAN_BYTES,
+        "v_add_u32 v22, s90, %[va]",
     ]
-    lines.append("s_cbranch_scc1 PATCH_%=")
-    jump(lines)
-
-
-def jump(lines):
+    for k in range(9):
+        b = INP + 4 * k
+        lines.append("ds_read_b128 v[%d:%d], v22 offset:%d" % (b, b + 3, k * QUAD_BYTES))
     lines += [
-        "s_and_b32 s90, s85, 0xff",
-        "s_min_u32 s90, s90, %d" % (SLOTS * len(CODE_MASKS) - 1),
-        "s_lshl_b32 s90, s90, %d" % STRIDE_LOG2,
+        "GO_%s_%%=:" % uid,
+        "s_and_b32 s90, s85, 0x%x" % (((1 << 20) - 1) << STRIDE_LOG2),
+        "s_min_u32 s90, s90, %d" % ((SLOTS * len(CODE_MASKS)) << STRIDE_LOG2),
         "s_add_u32 s94, s92, s90",
         "s_addc_u32 s95, s93, 0",
         "s_setpc_b64 s[94:95]",
@@ -71,33 +96,23 @@ def in_reg(row, col):
 def generate():
     L = []
     L += [
-        "s_cmp_ge_u32 %[first], %[cnt]",
-        "s_cbranch_scc1 DONE_%=",
         "s_getpc_b64 s[92:93]",
         "BASE_%=:",
         "s_add_u32 s92, s92, TABLE_%=-BASE_%=",
         "s_addc_u32 s93, s93, 0",
         "s_mov_b32 s84, %[first]",
+        "s_lshl_b32 s90, s84, 4",
+        "s_add_u32 s90, s90, %[wa]",
+        "v_mov_b32 v23, s90",
         # The records run at the lowest issue priority, everything around them (staging the next
-        # chunk, the counters that other waves wait for) at the highest: see DONE below.
+        # chunk, the counters that other waves wait for) at the highest: see the end.
         "s_setprio 0",
     ]
-    fetch(L)
-    # out of line: a new channel starts, reload the lane's 6x6 neighbourhood from LDS
-    L += [
-        "PATCH_%=:",
-        "s_bfe_u32 s90, s85, %[chbfe]",
-        "s_mul_i32 s90, s90, %d" % CHAN_BYTES,
-        "v_add_u32 v22, s90, %[va]",
-    ]
-    for k in range(9):
-        b = INP + 4 * k
-        L.append("ds_read_b128 v[%d:%d], v22 offset:%d" % (b, b + 3, k * QUAD_BYTES))
-    jump(L)
+    fetch(L, "first")
     L.append(".p2align %d" % STRIDE_LOG2)
     L.append("TABLE_%=:")
     for slot in range(SLOTS):
-        for mask in CODE_MASKS:
+        for ci, mask in enumerate(CODE_MASKS):
             L.append("s_waitcnt lgkmcnt(0)")
             j = 0
             for t in range(9):
@@ -109,14 +124,11 @@ def generate():
                         L.append("v_fmac_f32 v%d, v%d, v%d" % (ACC + 16 * slot + 4 * i + k, WREG + j,
                                                                in_reg(i + r, k + c)))
                 j += 1
-            L += [
-                "s_add_u32 s84, s84, 1",
-                "s_cmp_ge_u32 s84, %[cnt]",
-                "s_cbranch_scc1 DONE_%=",
-            ]
-            fetch(L)
+            L.append("s_add_u32 s84, s84, 1")
+            fetch(L, "%d_%d" % (slot, ci))
             L.append(".p2align %d" % STRIDE_LOG2)
-    L.append("DONE_%=:")
+    # the body of the end-of-list record: the loop is over (the weights fetched for it are not used)
+    L.append("s_waitcnt lgkmcnt(0)")
     L.append("s_setprio 3")
     return L
 
@@ -147,6 +159,18 @@ def generate_takeover():
     return L
 
 
+def write_code_header(path):
+    assert all(bin(m).count("1") <= 4 for m in CODE_MASKS)
+    with open(path, "w") as f:
+        f.write("// generated by gen_tiled_compute.py - do not edit\n")
+        f.write("constexpr int kNumCodes = %d;\n" % len(CODE_MASKS))
+        f.write("constexpr int kBodyStrideLog2 = %d;\n" % STRIDE_LOG2)
+        f.write("constexpr uint16_t kCodeMask[kNumCodes] = {\n")
+        for i in range(0, len(CODE_MASKS), 12):
+            f.write("    " + ", ".join("0x%03X" % m for m in CODE_MASKS[i:i + 12]) + ",\n")
+        f.write("};\n")
+
+
 def write_inc(path, lines):
     with open(path, "w") as f:
         f.write("// generated by gen_tiled_compute.py - do not edit\n")
@@ -159,6 +183,7 @@ def main():
     out = sys.argv[1]
     write_inc(out, generate())
     write_inc(os.path.join(os.path.dirname(out), "pconv_tiled_takeover.inc"), generate_takeover())
+    write_code_header(os.path.join(os.path.dirname(out), "pconv_tiled_code_masks.inc"))
 
 
 if __name__ == "__main__":

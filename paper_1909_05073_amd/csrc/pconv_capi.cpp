@@ -274,6 +274,22 @@ int pconv_conv2d_pool2x2(const pconv_handle *h, const void *x_dev, void *y_dev, 
                              fuse_relu ? 1 : 0, 1, hip_stream);
 }
 
+int pconv_pool2x2_fusion(const pconv_handle *h, int n, int h_in, int w_in, pconv_layout layout, pconv_dtype act_dtype)
+{
+    if (!h) { set_error("pconv_pool2x2_fusion: null pointer argument"); return PCONV_INVALID_ARG; }
+    if (n <= 0 || h_in <= 0 || w_in <= 0) { set_error("pconv_pool2x2_fusion: n, h_in and w_in must be positive"); return PCONV_INVALID_ARG; }
+    if (h->device < 0 || int(act_dtype) != h->wdtype || g_policy.load() == 1 ||
+        !tiled_pool_supported(h, n, h_in, w_in, int(layout), int(act_dtype)))
+        return 0;
+    return tiled_shares_units(h, n, h_in, w_in) ? 1 : 2;
+}
+
+int pconv_debug_measure_fma_peak(double *tflops)
+{
+    if (!tflops) { set_error("pconv_debug_measure_fma_peak: null pointer argument"); return PCONV_INVALID_ARG; }
+    return measure_fma_peak(tflops);
+}
+
 int pconv_maxpool2x2(const void *x_dev, void *y_dev, int n, int c, int h, int w,
                      pconv_layout layout, pconv_dtype dtype, void *hip_stream)
 {

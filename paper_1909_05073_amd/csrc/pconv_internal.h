@@ -98,6 +98,11 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
 // whether the tiled kernel can write the 2x2 max-pooled output directly (pool = 1)
 bool tiled_pool_supported(const pconv_handle *h, int n, int hin, int win, int layout, int dtype);
 bool tiled_supported(const pconv_handle *h, int n, int hin, int win, int stride, int layout, int dtype);
+// whether pconv_conv2d (fp32 NCHW, stride 1) would let workgroups share tiles of this call, which a
+// fused max-pool rules out
+bool tiled_shares_units(const pconv_handle *h, int n, int hin, int win);
+// plain vector-FMA rate of the device (see pconv_debug_measure_fma_peak)
+int measure_fma_peak(double *tflops);
 // whether the automatic policy should take the tiled kernel for a call it supports
 bool tiled_preferred(int hin, int win, int stride);
 // Test override of the tiled kernel's launch choices: waves per workgroup (8 or 16, anything else =

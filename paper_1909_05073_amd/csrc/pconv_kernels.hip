@@ -147,4 +147,69 @@ int launch_maxpool2x2(const void *x, void *y, int n, int c, int h, int w, int la
     return check_launch("pconv_maxpool2x2");
 }
 
+namespace {
+
+// 64 independent accumulators per lane, all operands in vector registers (an FMA with a scalar
+// operand issues at half the rate on this chip), 16 waves per compute unit: the rate the tiled
+// kernel's inner loops could reach with nothing else to do.
+__global__ void __launch_bounds__(1024) fma_peak_kernel(float *out, int iters)
+{
+    float acc[64];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) acc[i] = float(threadIdx.x + i);
+    float w0 = 1.0f + 1e-7f * float(threadIdx.x), w1 = 1.0f - 1e-7f * float(threadIdx.x);
+    float x0 = 1e-3f * float(threadIdx.x & 7), x1 = x0 + 0.5f;
+    asm volatile("" : "+v"(w0), "+v"(w1), "+v"(x0), "+v"(x1));
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 64; i += 2) {
+            acc[i] = fmaf(w0, x0, acc[i]);
+            acc[i + 1] = fmaf(w1, x1, acc[i + 1]);
+        }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 64; ++i) s += acc[i];
+    out[size_t(blockIdx.x) * blockDim.x + threadIdx.x] = s;
+}
+
+}  // namespace
+
+int measure_fma_peak(double *tflops)
+{
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+        set_error("pconv_debug_measure_fma_peak: no device");
+        return PCONV_HIP_ERROR;
+    }
+    const int blocks = cus * 4, threads = 1024, iters = 4000;
+    float *out = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void **>(&out), size_t(blocks) * threads * sizeof(float));
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    float best_ms = 0.0f;
+    for (int rep = 0; e == hipSuccess && rep < 3; ++rep) {
+        e = hipEventRecord(e0, nullptr);
+        if (e != hipSuccess) break;
+        hipLaunchKernelGGL(fma_peak_kernel, dim3(blocks), dim3(threads), 0, nullptr, out, iters);
+        e = hipGetLastError();
+        if (e == hipSuccess) e = hipEventRecord(e1, nullptr);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms = 0.0f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e == hipSuccess && rep > 0 && (best_ms == 0.0f || ms < best_ms)) best_ms = ms;
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (out) (void)hipFree(out);
+    if (e != hipSuccess || best_ms <= 0.0f) {
+        set_error(std::string("pconv_debug_measure_fma_peak: ") + hipGetErrorName(e));
+        return PCONV_HIP_ERROR;
+    }
+    *tflops = 2.0 * 64 * iters * double(blocks) * threads / (double(best_ms) * 1e-3) / 1e12;
+    return PCONV_OK;
+}
+
 }  // namespace pconv

@@ -236,7 +236,7 @@ void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int 
                 const int32_t k = by_slot[s][c];
                 if (k < 0) continue;
                 for (const Piece &pc : pieces[cn.pat[k]]) {
-                    out.meta.push_back(uint32_t(s * kNumCodes + pc.code) | uint32_t(c % kTileCH) << 8 |
+                    out.meta.push_back(uint32_t(s * kNumCodes + pc.code) << kMetaCaseShift | uint32_t(c % kTileCH) |
                                        (first ? kMetaFirstOfChannel : 0u));
                     first = false;
                     for (int j = 0; j < 4; ++j) {

@@ -65,8 +65,8 @@ template <int NW, int CH> struct Shape {
     static_assert(CH * 6 % NW == 0 && UNITS % 8 == 0 && CH <= kTileCH && kTileCH % CH == 0, "unsupported shape");
 };
 
-static_assert(kNumCodes == 24 && FB == 4 && BATCH == 32 && kTileCH == 8,
-              "gen_tiled_compute.py is written for 24 codes, 4 slots, 32-record batches, channel field of 3 bits");
+static_assert(FB == 4 && BATCH == 32 && kTileCH == 8,
+              "gen_tiled_compute.py is written for 4 slots, 32-record batches, channel field of 3 bits");
 
 __device__ __forceinline__ float ld_act(const float *p, size_t i) { return p[i]; }
 __device__ __forceinline__ float ld_act(const bf16_t *p, size_t i) { return __uint_as_float(uint32_t(p[i].bits) << 16); }
@@ -412,8 +412,30 @@ conv_tiled_kernel(const TiledArgs a)
         // ---- the records of one chunk: generated assembly, in batches of up to BATCH records ----
         auto compute = [&](int rel, uint32_t k0, uint32_t k_cnt, uint32_t rec_m) {
             const uint32_t buf_bytes = uint32_t(rel & 1) * uint32_t(BUF_FLOATS * 4);
-            for (uint32_t base = 0; base < k_cnt; base += BATCH) {
-                if (base > 0) {
+            // (one loop around a single copy of the assembly: the refill of a further batch sits behind it)
+            uint32_t base = 0;
+            while (base < k_cnt) {
+                const uint32_t nb = min(uint32_t(BATCH), k_cnt - base);
+                // lane j = record j of the batch; the lanes behind the last record end the list
+                const uint32_t rm = uint32_t(fresh_lane()) < nb ? rec_m : kMetaEndOfList;
+                uint32_t first = 0;                      // (kept apart from other zero operands)
+                asm volatile("" : "+s"(first));
+                asm volatile(
+#include "pconv_tiled_compute.inc"
+                    : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
+                    : [recm] "v"(rm), [va] "v"(lds_base + buf_bytes + uint32_t(fresh_lane()) * 16u),
+                      [wa] "s"(wa), [first] "s"(first), [chmask] "n"(CH - 1)
+                    : "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
+                      "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45",
+                      "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57",
+                      "v58", "v59", "v60", "v61", "v62", "v63",
+                      "s84", "s85", "s90", "s91", "s92", "s93", "s94", "s95", "scc");
+                // No "memory" clobber on purpose: it would make the compiler wait for the
+                // global->LDS loads of the next chunk, which may be in flight here and go to the
+                // other buffer.  What the loop reads was published before (barrier / counters), or
+                // written by the volatile stores below.
+                base += BATCH;
+                if (base < k_cnt) {
                     // more than BATCH records in this chunk (rare): next batch (the wave's weight
                     // block is private, and LDS accesses of one wave execute in order)
                     const uint32_t ridx = k0 + min(base + uint32_t(fresh_lane()), k_cnt);
@@ -428,21 +450,6 @@ conv_tiled_kernel(const TiledArgs a)
                         wv[0] = rec_w.x; wv[1] = rec_w.y; wv[2] = rec_w.z; wv[3] = rec_w.w;
                     }
                 }
-                const uint32_t nb = __builtin_amdgcn_readfirstlane(min(uint32_t(BATCH), k_cnt - base));
-                asm volatile(
-#include "pconv_tiled_compute.inc"
-                    : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
-                    : [recm] "v"(rec_m), [va] "v"(lds_base + buf_bytes + uint32_t(fresh_lane()) * 16u),
-                      [wa] "s"(wa), [first] "s"(0u), [cnt] "s"(nb), [chbfe] "n"(CH == 8 ? 0x30008 : 0x20008)
-                    : "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
-                      "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45",
-                      "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57",
-                      "v58", "v59", "v60", "v61", "v62", "v63",
-                      "s84", "s85", "s90", "s91", "s92", "s93", "s94", "s95", "scc");
-                // No "memory" clobber on purpose: it would make the compiler wait for the
-                // global->LDS loads of the next chunk, which may be in flight here and go to the
-                // other buffer.  What the loop reads was published before (barrier / counters), or
-                // written by the volatile stores in the batch path.
             }
         };
 
@@ -520,7 +527,7 @@ conv_tiled_kernel(const TiledArgs a)
                 compute(rel, k0, k_cnt, rec_m);
                 // every LDS read of this chunk has returned (the record loop waits for its loads)
                 if (more) {
-                    if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
+                    { const int lw = fresh_lane(); if (lw < BATCH) *reinterpret_cast<float4 *>(wlds + lw * 4) = nrec_w; }
                     k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
                     help_stage(rel + 1, true);
                 }
@@ -546,7 +553,7 @@ conv_tiled_kernel(const TiledArgs a)
                 }
                 compute(rel, k0, k_cnt, rec_m);
                 if (more) {
-                    if (lane < BATCH) *reinterpret_cast<float4 *>(wlds + lane * 4) = nrec_w;
+                    { const int lw = fresh_lane(); if (lw < BATCH) *reinterpret_cast<float4 *>(wlds + lw * 4) = nrec_w; }
                     k0 = nk0; k_cnt = nk_cnt; rec_m = nrec_m;
                     __syncthreads();
                 }
@@ -853,6 +860,20 @@ uint32_t *static_flags(int dev)
 std::atomic<uint32_t> g_static_calls{0};             // epochs of the calls that use `scratch`
 
 }  // namespace
+
+bool tiled_shares_units(const pconv_handle *h, int n, int hin, int win)
+{
+    // the automatic choice of launch_conv_tiled for an fp32 NCHW call with stride 1 and no fused pool
+    const int py = (hin + 3) / 4, px = (win + 3) / 4;
+    const int64_t n_tiles = (int64_t(n) * py * px + 63) / 64;
+    const int64_t x_bytes = int64_t(n) * h->c_in * hin * win * 4, y_bytes = int64_t(n) * h->c_out * hin * win * 4;
+    const bool vec = win >= 4 && x_bytes < (int64_t(1) << 31);
+    const int nw = h->c_in <= 4 ? 8 : 16;
+    const int slots = (h->cus > 0 ? h->cus : 256) * (16 / nw);
+    const bool rows_whole = win % 4 == 0 || n_tiles == 1 || 64 % px == 0;
+    return vec && y_bytes < (int64_t(1) << 31) && rows_whole &&
+           n_tiles * ((h->tiled.num_blocks + nw - 1) / nw) <= slots / 2;
+}
 
 int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float *bias, int n,
                       int hin, int win, int stride, int layout, int dtype, int relu, int pool, void *stream,

@@ -302,6 +302,36 @@ def test_four_scp_table():
             check_full(spec, L, x, "f32", relu=True, policy=policy, what=f"scp4_{j}")
 
 
+def test_tables_of_random_masks():
+    """Pattern tables drawn at random, as in the paper's pattern-count experiment ("random patterns
+    with 4 non-zero elements"): 4-tap masks with the centre (one work item per kernel), 4-tap masks
+    without it, and masks of 2 to 7 taps (split into several items at pack time)."""
+    rng = np.random.default_rng(99)
+    centred = [m for m in range(512) if bin(m).count("1") == 4 and (m >> 4) & 1]
+    free4 = [m for m in range(512) if bin(m).count("1") == 4 and not (m >> 4) & 1]
+    other = [m for m in range(1, 512) if bin(m).count("1") in (2, 3, 5, 6, 7)]
+    tables = [rng.choice(centred, 8, replace=False), rng.choice(centred, 16, replace=False),
+              rng.choice(free4, 8, replace=False), rng.choice(other, 12, replace=False)]
+    for j, table in enumerate(tables):
+        table = np.asarray(table, np.uint16)
+        f, c = 72, 40
+        L = dict(w=rng.standard_normal((f, c, 3, 3)).astype(np.float32),
+                 bias=rng.standard_normal(f).astype(np.float32),
+                 pattern_id=rng.integers(0, len(table), (f, c)).astype(np.uint8),
+                 conn=(rng.random((f, c)) < 0.4).astype(np.uint8), table=table)
+        spec = LayerSpec(f"randtable{j}", 2, c, f, 13, 16)
+        x = make_input(spec, 8000 + j) - 0.3
+        for policy in POLICIES:
+            check_full(spec, L, x, "f32", relu=bool(j & 1), policy=policy, what=f"random table {j}")
+        h = P.pconv_pack(L["w"], L["pattern_id"], L["conn"], table, "f32")
+        _, records = P.pconv_debug_export_blocks(h)
+        kept = int(L["conn"].sum())
+        say(f"[info] random table {j}: {int(records.sum())} work items for {kept} kernels")
+        if j < 2:
+            assert int(records.sum()) == kept         # one item per kernel for centred 4-tap masks
+        h.free()
+
+
 def test_expired_wait_is_reported_by_the_next_call():
     """Error path, forced from the host: with a spin limit of 1 every bounded wait inside the tiled
     kernel gives up at once.  The kernels still run to their end; the handle reports the failure
