@@ -133,3 +133,18 @@ def unpack(packed, table, c_in, wdtype="f32"):
                      _p(packed["cin"]), _p(packed["vals"]), _p(tb), C.c_int(len(tb)),
                      C.c_int(f), C.c_int(c_in), C.c_int(_DTYPE[wdtype]), _p(w))
     return w
+
+
+def project(w, table, keep: int):
+    """Euclidean projection of dense weights [F][C][3][3] onto (pattern table, `keep` kernels):
+    returns (pattern_id [F][C] uint8, conn [F][C] uint8).  See pconv_project_oracle.c."""
+    w = _c(w, np.float32)
+    tb = _c(table, np.uint16)
+    f, c = w.shape[:2]
+    pid = np.zeros((f, c), np.uint8)
+    conn = np.zeros((f, c), np.uint8)
+    fn = lib().orc_project
+    fn.restype = None
+    fn.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_long, C.c_void_p, C.c_void_p]
+    fn(_p(w), _p(tb), int(tb.size), int(f), int(c), int(keep), _p(pid), _p(conn))
+    return pid, conn
