@@ -68,6 +68,28 @@ int pconv_pack(const float *w_dense, const uint8_t *pattern_id, const uint8_t *c
                pconv_dtype weight_dtype, pconv_handle **out);
 
 /*
+ * pconv_project - the step before pconv_pack: gives dense 3x3 weights their PCONV form, as the
+ * Euclidean projection that an ADMM pruner for the paper's two constraints repeats ("Accuracy
+ * Analysis": the models are produced by an ADMM framework extended to pattern and connectivity
+ * pruning; the paper's own algorithm text is in supplemental material).  Per kernel the table
+ * pattern is chosen under which the kernel keeps the largest sum of squared weights (the first
+ * such pattern among equals); then the keep_kernels kernels that keep the most under their
+ * pattern survive (the smaller f * c_in + c among equals).  Sums are formed in double over the
+ * taps in ascending order.  Host only, synchronous, no GPU needed.
+ *
+ *   w_dense          host, [c_out][c_in][3][3] fp32
+ *   table            host, [num_patterns] 9-bit masks as for pconv_pack
+ *   keep_kernels     0 .. c_out * c_in: number of kernels connectivity pruning leaves
+ *   pattern_id_out   host, [c_out][c_in], written for every kernel
+ *   conn_out         host, [c_out][c_in], 1 = kept, 0 = removed
+ *
+ * The outputs, with w_dense itself, are what pconv_pack takes (it ignores the weights under
+ * cleared mask bits and on removed kernels).  Errors: PCONV_INVALID_ARG, PCONV_OOM.
+ */
+int pconv_project(const float *w_dense, const uint16_t *table, int num_patterns, int c_out, int c_in,
+                  int64_t keep_kernels, uint8_t *pattern_id_out, uint8_t *conn_out);
+
+/*
  * pconv_conv2d - the sparse convolution itself (Eq. (1) over the packed weights; the
  * "load redundancy elimination" stage of the paper: only inputs under kept taps of kept
  * kernels are touched).  Asynchronous on hip_stream; allocates nothing.  The packed weights in

@@ -54,6 +54,8 @@ def lib():
     vp, ip = C.c_void_p, C.c_int
     L.pconv_pack.restype = ip
     L.pconv_pack.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, C.POINTER(vp)]
+    L.pconv_project.restype = ip
+    L.pconv_project.argtypes = [vp, vp, ip, ip, ip, C.c_int64, vp, vp]
     L.pconv_debug_pack_host.restype = ip
     L.pconv_debug_pack_host.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, C.POINTER(vp)]
     L.pconv_conv2d.restype = ip
@@ -92,7 +94,7 @@ def lib():
     return L
 
 
-EXPORTED_SYMBOLS = ["pconv_pack", "pconv_conv2d", "pconv_conv2d_static", "pconv_conv2d_pool2x2", "pconv_free", "pconv_maxpool2x2",
+EXPORTED_SYMBOLS = ["pconv_project", "pconv_pack", "pconv_conv2d", "pconv_conv2d_static", "pconv_conv2d_pool2x2", "pconv_free", "pconv_maxpool2x2",
                     "pconv_get_info", "pconv_debug_export", "pconv_debug_export_blocks", "pconv_debug_pack_host",
                     "pconv_debug_unpack",
                     "pconv_set_kernel_policy", "pconv_debug_set_tiling", "pconv_debug_set_spin_limit",
@@ -148,6 +150,19 @@ def pconv_pack(w_dense, pattern_id, conn, table, weight_dtype="f32", host_only=F
             int(tb.size), int(w.shape[0]), int(w.shape[1]), _DTYPE[weight_dtype], C.byref(out))
     _check(rc)
     return Handle(out.value, int(w.shape[0]), int(w.shape[1]), _DTYPE[weight_dtype])
+
+
+def pconv_project(w_dense, table, keep_kernels: int):
+    """Dense weights [F][C][3][3] -> (pattern_id [F][C] uint8, conn [F][C] uint8); see include/pconv.h."""
+    w = _np(w_dense, np.float32)
+    tb = _np(table, np.uint16)
+    if w.ndim != 4 or w.shape[2:] != (3, 3):
+        raise ValueError("expected w [F][C][3][3]")
+    pid = np.empty(w.shape[:2], np.uint8)
+    conn = np.empty(w.shape[:2], np.uint8)
+    _check(lib().pconv_project(w.ctypes.data, tb.ctypes.data, int(tb.size), int(w.shape[0]), int(w.shape[1]),
+                               int(keep_kernels), pid.ctypes.data, conn.ctypes.data))
+    return pid, conn
 
 
 def pconv_conv2d(handle: Handle, x_ptr: int, y_ptr: int, bias_ptr, n: int, h_in: int, w_in: int,

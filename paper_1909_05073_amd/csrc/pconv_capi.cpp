@@ -175,6 +175,23 @@ int pconv_pack(const float *w_dense, const uint8_t *pattern_id, const uint8_t *c
     return pack_impl(w_dense, pattern_id, conn, table, num_patterns, c_out, c_in, weight_dtype, out, true);
 }
 
+int pconv_project(const float *w_dense, const uint16_t *table, int num_patterns, int c_out, int c_in,
+                  int64_t keep_kernels, uint8_t *pattern_id_out, uint8_t *conn_out)
+{
+    if (!w_dense || !table || !pattern_id_out || !conn_out) { set_error("pconv_project: null pointer argument"); return PCONV_INVALID_ARG; }
+    if (num_patterns < 1 || num_patterns > PCONV_MAX_PATTERNS) { set_error("pconv_project: num_patterns must be 1..16"); return PCONV_INVALID_ARG; }
+    if (c_out < 1 || c_out > 65535 || c_in < 1 || c_in > 65535) { set_error("pconv_project: c_out and c_in must be 1..65535"); return PCONV_INVALID_ARG; }
+    if (keep_kernels < 0 || keep_kernels > int64_t(c_out) * c_in) { set_error("pconv_project: keep_kernels must be 0..c_out*c_in"); return PCONV_INVALID_ARG; }
+    for (int p = 0; p < num_patterns; ++p)
+        if (table[p] == 0 || table[p] > 0x1FF) { set_error("pconv_project: table entries must be non-zero 9-bit masks"); return PCONV_INVALID_ARG; }
+    try {
+        return project_weights(w_dense, table, num_patterns, c_out, c_in, keep_kernels, pattern_id_out, conn_out);
+    } catch (const std::bad_alloc &) {
+        set_error("pconv_project: out of host memory");
+        return PCONV_OOM;
+    }
+}
+
 int pconv_debug_pack_host(const float *w_dense, const uint8_t *pattern_id, const uint8_t *conn,
                           const uint16_t *table, int num_patterns, int c_out, int c_in,
                           pconv_dtype weight_dtype, pconv_handle **out)

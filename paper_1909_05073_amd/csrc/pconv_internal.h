@@ -85,6 +85,9 @@ namespace pconv {
 int build_canonical(const float *w, const uint8_t *pid, const uint8_t *conn, const uint16_t *table,
                     int np, int c_out, int c_in, int wdtype, Canonical &out);
 
+int project_weights(const float *w, const uint16_t *table, int np, int c_out, int c_in, int64_t keep,
+                    uint8_t *pattern_id, uint8_t *conn);
+
 void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int c_out, int c_in,
                         TiledStream &out);
 

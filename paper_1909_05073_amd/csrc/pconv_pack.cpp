@@ -276,4 +276,41 @@ void build_dense_taps(const Canonical &cn, const uint16_t *table, int c_out, int
     }
 }
 
+// ---- projection of dense weights onto the PCONV constraints ------------------------------
+//
+// Pattern assignment: the table mask under which a kernel keeps the most energy (sum of squares of
+// the kept taps; the first such mask among equals).  Connectivity: the `keep` kernels that keep the
+// most energy under their mask survive (the lower (f, c) among equals).  Energies are accumulated in
+// double over the taps in ascending order, so equal inputs decide equally everywhere.
+int project_weights(const float *w, const uint16_t *table, int np, int c_out, int c_in, int64_t keep,
+                    uint8_t *pattern_id, uint8_t *conn)
+{
+    const size_t total = size_t(c_out) * c_in;
+    std::vector<double> energy(total);
+    for (size_t k = 0; k < total; ++k) {
+        double sq[9];
+        for (int t = 0; t < 9; ++t) sq[t] = double(w[9 * k + t]) * double(w[9 * k + t]);
+        int arg = 0;
+        double top = -1.0;
+        for (int p = 0; p < np; ++p) {
+            double e = 0.0;
+            for (unsigned m = table[p], t = 0; m; m >>= 1, ++t)
+                if (m & 1u) e += sq[t];
+            if (e > top) { top = e; arg = p; }
+        }
+        pattern_id[k] = uint8_t(arg);
+        energy[k] = top;
+    }
+    std::fill(conn, conn + total, uint8_t(0));
+    if (keep <= 0) return PCONV_OK;
+    std::vector<uint32_t> order(total);
+    std::iota(order.begin(), order.end(), 0u);
+    const size_t kk = std::min<size_t>(size_t(keep), total);
+    // (a strict order: energy descending, then index ascending - the kept set does not depend on the algorithm)
+    auto before = [&](uint32_t a, uint32_t b) { return energy[a] != energy[b] ? energy[a] > energy[b] : a < b; };
+    if (kk < total) std::nth_element(order.begin(), order.begin() + kk, order.end(), before);
+    for (size_t i = 0; i < kk; ++i) conn[order[i]] = 1;
+    return PCONV_OK;
+}
+
 }  // namespace pconv
