@@ -244,8 +244,10 @@ int pconv_set_kernel_policy(int policy);
 /* pconv_debug_set_tiling - for tests: pins launch choices the register-tiled kernel otherwise
  * makes per call.  waves = 8 or 16 (workgroup size in waves; 0 = automatic); ks_log2 = 0, 1 or 2
  * (the waves of a workgroup split the input channels 1, 2 or 4 ways; -1 = automatic);
- * split_units = 0 or 1 (whether several workgroups may share one tile of outputs, each taking a
- * range of the input channels; -1 = automatic).  Values out of range mean automatic.
+ * split_units = 0, 1 or 2 (whether several workgroups may share one tile of outputs, each taking a
+ * range of the input channels: 0 = never, 1 = yes, with the work dealt out per group of workgroups
+ * that share a level-2 cache, 2 = yes, dealt out evenly over all workgroups; -1 = automatic).
+ * Values out of range mean automatic.
  * Process-wide; results are the same for every choice up to the order of the fp32 additions. */
 int pconv_debug_set_tiling(int waves, int ks_log2, int split_units);
 

@@ -97,6 +97,7 @@ struct TiledArgs {
     int n_units;                // n_tiles * n_groups: (tile, filter group) pairs
     int n_chunks;               // chunks of CH input channels
     int split_units;            // 1: a workgroup's share of the work may begin and end inside a unit
+    int one_set;                // 1 (with split_units): the iterations are dealt over all workgroups as one set
     uint32_t *flags;            // [gridDim.x] hand-over words of this call (split_units only)
     uint32_t epoch;             // value that marks a hand-over word as set by this call (never 0)
     uint32_t x_bytes;           // size of the input tensor (VEC kernel: below 2^31)
@@ -181,12 +182,16 @@ conv_tiled_kernel(const TiledArgs a)
     const int n_chunks = a.n_chunks;
 
     // ---- this workgroup's range of iterations ----
-    const int set = blockIdx.x & 7, j_in_set = blockIdx.x >> 3;
-    const int set_units = ((a.n_tiles - set + 7) >> 3) * a.n_groups;         // tiles set, set + 8, ...
+    // (one_set: no XCD sets - the shares of all workgroups are then equal whatever the number of tiles,
+    // and the workgroup that a piece waits for is simply the one before it)
+    const bool one_set = SPLIT && a.one_set;
+    const int set = one_set ? 0 : int(blockIdx.x & 7), j_in_set = one_set ? int(blockIdx.x) : int(blockIdx.x >> 3);
+    const int set_stride = one_set ? 1 : 8;
+    const int set_units = one_set ? a.n_units : ((a.n_tiles - set + 7) >> 3) * a.n_groups;   // tiles set, set + 8, ...
     // SPLIT: iteration = (unit of the set) * n_chunks + chunk; otherwise one whole unit per workgroup
     int ua = j_in_set, ub = j_in_set, head_c0 = 0, tail_c1 = n_chunks;
     if constexpr (SPLIT) {
-        const int wgs_in_set = (int(gridDim.x) - set + 7) >> 3;
+        const int wgs_in_set = one_set ? int(gridDim.x) : (int(gridDim.x) - set + 7) >> 3;
         const int64_t iters = int64_t(set_units) * n_chunks;
         const int64_t takers = iters < wgs_in_set ? iters : wgs_in_set;       // nobody gets an empty range in between
         if (j_in_set >= takers) return;
@@ -222,7 +227,7 @@ conv_tiled_kernel(const TiledArgs a)
         else if (piece - (has_tail ? 1 : 0) < n_whole) unit = first_whole + piece - (has_tail ? 1 : 0);
         else { unit = ua; c_begin = head_c0; }
         const bool takes_over = SPLIT && c_begin > 0, hands_on = SPLIT && c_end < n_chunks;
-        const int tile = (unit / a.n_groups) * 8 + set, group = unit % a.n_groups;
+        const int tile = (unit / a.n_groups) * set_stride + set, group = unit % a.n_groups;
         const int fblk = group * fw + (wave - ksplit * fw);
         const bool active = fblk < a.n_blocks;
 
@@ -309,6 +314,7 @@ conv_tiled_kernel(const TiledArgs a)
             const int ln = fresh_lane();
             const int ch = sunit >> 1, half = sunit & 1;
             if (c0 + ch >= a.c_in) return;                               // (uniform)
+
             const uint32_t soff = __builtin_amdgcn_readfirstlane(uint32_t(c0 + ch) * uint32_t(hw) * 4u);
             float *cbuf = buf + ch * CHAN_FLOATS;
             // everything the lane needs from the tables first, so that there is one wait for LDS
@@ -404,6 +410,7 @@ conv_tiled_kernel(const TiledArgs a)
             }
             k0 = __builtin_amdgcn_readlane(ptr_lo, chunk - win_base);
             k_cnt = active ? __builtin_amdgcn_readlane(ptr_hi, chunk - win_base) - k0 : 0u;
+
             const uint32_t ridx = k0 + min(uint32_t(lane), k_cnt);
             rec_m = a.meta[ridx];
             rec_w = a.w4[ridx];
@@ -479,7 +486,7 @@ conv_tiled_kernel(const TiledArgs a)
                     const unsigned v = __builtin_amdgcn_readfirstlane(
                         __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
                     if (v >= target) { reached = true; break; }
-                    __builtin_amdgcn_s_sleep(2);
+                    __builtin_amdgcn_s_sleep(4);
                 }
                 if (!reached && fresh_lane() == 0) {
                     __hip_atomic_store(&sync_words[6], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -610,7 +617,7 @@ conv_tiled_kernel(const TiledArgs a)
                 if (wave == 0) {
                     bool there = false;
                     for (int guard = 0; guard < (a.spin_limit >> 2) && !there; ++guard) {
-                        there = __hip_atomic_load(a.flags + (blockIdx.x - 8), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
+                        there = __hip_atomic_load(a.flags + (blockIdx.x - set_stride), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch;
                         if (!there) __builtin_amdgcn_s_sleep(8);
                     }
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -793,6 +800,7 @@ hipError_t launch_any(const TiledArgs &a, int64_t wgs, hipStream_t st, bool vec,
 
 // test overrides, see set_tiled_tuning / set_tiled_spin_limit
 std::atomic<int> g_force_waves{0}, g_force_ks{-1}, g_force_split{-1};
+constexpr double kShareGain = 0.97;
 constexpr int kDefaultSpinLimit = 1 << 22;
 std::atomic<int> g_spin_limit{kDefaultSpinLimit};
 
@@ -802,7 +810,7 @@ void set_tiled_tuning(int waves, int ks_log2, int split_units)
 {
     g_force_waves.store((waves == 8 || waves == 16) ? waves : 0);
     g_force_ks.store((ks_log2 >= 0 && ks_log2 <= 2) ? ks_log2 : -1);
-    g_force_split.store((split_units == 0 || split_units == 1) ? split_units : -1);
+    g_force_split.store((split_units >= 0 && split_units <= 2) ? split_units : -1);
 }
 
 void set_tiled_spin_limit(int limit) { g_spin_limit.store(limit > 0 ? limit : kDefaultSpinLimit); }
@@ -916,8 +924,24 @@ int launch_conv_tiled(const pconv_handle *h, const void *x, void *y, const float
     const bool rows_whole = win % 4 == 0 || a.n_tiles == 1 || 64 % a.px == 0;
     const bool can_split = vec && !pool && !a.sub2 && y_bytes < (int64_t(1) << 31) && rows_whole;
     a.y_bytes = uint32_t(std::min<int64_t>(y_bytes, 0x7FFFFFFF));
-    a.split_units = can_split && int64_t(a.n_tiles) * ((a.n_blocks + nw - 1) / nw) <= slots / 2;
-    if (force_split >= 0) a.split_units = can_split ? force_split : 0;
+    const int64_t whole_units = int64_t(a.n_tiles) * ((a.n_blocks + nw - 1) / nw);
+    a.split_units = can_split && whole_units <= slots / 2;
+    a.one_set = 0;
+    if (can_split && !a.split_units && nw == 16) {
+        // Many units, but not a multiple of the number of compute units: whole units leave part of
+        // the chip idle in the last round.  Dealing the chunks of all units evenly (every workgroup
+        // one contiguous share, over all workgroups as one set) was measured to cost each workgroup
+        // the time of about ten chunks (further start-ups, the partial sums through memory with a
+        // device-wide release and acquire); a last round with few units runs faster than a full
+        // one (measured: 0.87 of it at 53 % busy).  So it pays for few, long units only (VGG
+        // conv9: 200 units of 64 chunks, -4 %).
+        constexpr double kShareOverhead = 10.0;
+        const double full = double(whole_units / slots), rest = double(whole_units % slots) / slots;
+        const double t_whole = a.n_chunks * (full + (rest > 0.0 ? 0.72 + 0.28 * rest : 0.0));
+        const double t_share = double(whole_units) * a.n_chunks / slots + kShareOverhead;
+        if (t_share < kShareGain * t_whole) { a.split_units = 1; a.one_set = 1; }
+    }
+    if (force_split >= 0) { a.split_units = can_split ? (force_split != 0) : 0; a.one_set = a.split_units && force_split == 2; }
     a.ks_log2 = 0;
     if (!a.split_units)
         while (a.ks_log2 < 2 && int64_t(a.n_tiles) * ((a.n_blocks + (nw >> a.ks_log2) - 1) / (nw >> a.ks_log2)) <= slots / 2)

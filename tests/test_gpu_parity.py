@@ -244,7 +244,7 @@ TILING_SHAPES = [  # (n, c_in, c_out, h, w): several chunks and filter groups, r
 ]
 
 
-@pytest.mark.parametrize("split_units", [0, 1])
+@pytest.mark.parametrize("split_units", [0, 1, 2])
 @pytest.mark.parametrize("ks_log2", [0, 1, 2])
 @pytest.mark.parametrize("waves", [8, 16])
 def test_tiled_kernel_every_workgroup_shape_and_channel_split(waves, ks_log2, split_units):
@@ -280,7 +280,7 @@ def test_more_than_64_chunks_of_input_channels(waves, c_in, split_units):
 # multiple of 4: there the last patch of a row overlaps its neighbour, and when the two lie in
 # different tiles the library must not let their workgroups pass partial sums through the
 # columns they share (it then keeps whole units).
-@pytest.mark.parametrize("split_units", [-1, 1])
+@pytest.mark.parametrize("split_units", [-1, 1, 2])
 @pytest.mark.parametrize("shape", [(4, 256, 64, 18, 18), (32, 256, 256, 10, 10), (3, 96, 64, 20, 24),
                                    (6, 72, 128, 14, 14), (2, 64, 64, 30, 26)])
 def test_shared_units_on_several_tiles(shape, split_units):
