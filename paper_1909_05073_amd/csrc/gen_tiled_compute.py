@@ -15,18 +15,24 @@ pins / clobbers the same registers):
     v[52 + r], v[58 + r]            the halo columns x0-1 and x0+4 of row r
     v[24:27]                        the record's four weights (same value in every lane)
     v22 LDS address of the patch, v23 LDS address of the next record's weights
-    s84 record index, s85 record word, s90 scratch, s[92:93] address of body 0, s[94:95] target
-Operands: %[recm] per-lane record words (lane j = record j), %[va] per-lane LDS byte address of
+    s84 record index, s85 record word, s86 the word after it, s90 scratch, s91 byte offset of the
+    word being loaded, s[92:93] address of body 0, s[94:95] target
+Operands: %[recm] per-lane record words (lane j = record j; only lanes 0 and 1 are read), %[mp]
+address of the record stream in global memory (SGPR pair) and %[koff] byte offset of record 0 in
+it (SGPR; words 2.. are read from there with scalar
+loads, because moving a lane of a vector register to a scalar register costs about a tenth of the
+loop's rate on this chip; up to two words behind the list are read and not used), %[nb] number
+of records (SGPR), %[va] per-lane LDS byte address of
 the lane's patch in the staged buffer (a staged channel is nine 1 KiB blocks of one 16-byte
 quad per lane: the six rows, then the twelve halo values), %[wa] LDS byte address
-of this wave's weight block (SGPR; 16 bytes per record), %[first] the first record to run (SGPR),
+of this wave's weight block (SGPR; 16 bytes per record),
 %[chmask] channels per chunk - 1 (immediate; 7 or 3).
 
 Record word: bits 0-2 the channel within its chunk, bit 3 set on the first record of a channel (the
 lane's 6x6 neighbourhood is then reloaded from LDS before the record runs), bits 9 and up the case
 (slot * codes + code) times the body stride, i.e. the byte offset of the record's body in the
-table.  The list ends with a record whose case is one past the last body: its "body" is the end of
-the loop, so the loop itself counts nothing.
+table.  Record number %[nb] is replaced by a word whose case is one past the last body: its "body"
+is the end of the loop.
 """
 import sys
 
@@ -63,8 +69,17 @@ def fetch(lines, uid):
     lines += [
         "ds_read_b128 v[%d:%d], v23" % (WREG, WREG + 3),
         "v_add_u32 v23, 16, v23",
-        "v_readlane_b32 s85, %[recm], s84",
-        "s_nop 0",
+    ]
+    if uid != "first":
+        # s86 holds the word of record s84, asked for one body ago; the word after it is asked
+        # for now and lands while this record's body runs
+        lines += [
+            "s_cmp_lt_u32 s84, %[nb]",
+            "s_cselect_b32 s85, s86, %d" % ((SLOTS * len(CODE_MASKS)) << STRIDE_LOG2),
+            "s_add_u32 s91, s91, 4",
+            "s_load_dword s86, %[mp], s91",
+        ]
+    lines += [
         "s_bitcmp1_b32 s85, 3",
         "s_cbranch_scc0 GO_%s_%%=" % uid,
         "s_and_b32 s90, s85, %[chmask]",
@@ -100,10 +115,13 @@ def generate():
         "BASE_%=:",
         "s_add_u32 s92, s92, TABLE_%=-BASE_%=",
         "s_addc_u32 s93, s93, 0",
-        "s_mov_b32 s84, %[first]",
-        "s_lshl_b32 s90, s84, 4",
-        "s_add_u32 s90, s90, %[wa]",
-        "v_mov_b32 v23, s90",
+        "s_mov_b32 s84, 0",
+        "v_mov_b32 v23, %[wa]",
+        # the first two record words come from the lanes of a register that was loaded a chunk
+        # ahead; every later word comes through the scalar cache, one body ahead of its use
+        "v_readlane_b32 s85, %[recm], 0",
+        "v_readlane_b32 s86, %[recm], 1",
+        "s_add_u32 s91, %[koff], 4",
         # The records run at the lowest issue priority, everything around them (staging the next
         # chunk, the counters that other waves wait for) at the highest: see the end.
         "s_setprio 0",

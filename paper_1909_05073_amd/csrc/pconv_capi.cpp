@@ -133,7 +133,10 @@ static int pack_impl(const float *w_dense, const uint8_t *pattern_id, const uint
                         h->canon.vals_bits.size(), h->device_bytes);
         if (rc == PCONV_OK) rc = upload(h->d_slot_filter, h->tiled.slot_filter.data(), h->tiled.slot_filter.size(), h->device_bytes);
         if (rc == PCONV_OK) rc = upload(h->d_chan_ptr, h->tiled.chan_ptr.data(), h->tiled.chan_ptr.size(), h->device_bytes);
-        if (rc == PCONV_OK) rc = upload(h->d_meta, h->tiled.meta.data(), h->tiled.meta.size(), h->device_bytes);
+        // (the tiled kernel keeps a record index in 24 bits: a longer stream stays off the device,
+        //  and the layer runs on the general kernels)
+        if (rc == PCONV_OK && h->tiled.meta.size() < (size_t(1) << 24))
+            rc = upload(h->d_meta, h->tiled.meta.data(), h->tiled.meta.size(), h->device_bytes);
         if (rc == PCONV_OK) rc = upload(h->d_w4, h->tiled.w4.data(), h->tiled.w4.size(), h->device_bytes);
         if (rc == PCONV_OK && weight_dtype == PCONV_BF16) {
             std::vector<uint16_t> wd; std::vector<uint32_t> nz;

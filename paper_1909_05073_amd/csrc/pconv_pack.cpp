@@ -249,8 +249,8 @@ void build_tiled_stream(const Canonical &cn, const uint16_t *table, int np, int 
         }
         for (int c = c_in; c <= cpad; ++c) row[c] = uint32_t(out.meta.size());
     }
-    // one padding record: the kernel reads record k+1 while it executes record k
-    out.meta.push_back(0u);
+    // padding: the kernel asks for the words of records k+1 and k+2 while it executes record k
+    for (int j = 0; j < 3; ++j) out.meta.push_back(0u);
     for (int j = 0; j < 4; ++j) out.w4.push_back(0.0f);
 }
 

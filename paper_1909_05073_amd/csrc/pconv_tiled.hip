@@ -241,13 +241,18 @@ conv_tiled_kernel(const TiledArgs a)
 
         // The records of a (filter block, chunk) are contiguous and ordered by channel, so this wave's
         // share of a chunk is the range between two entries of chan_ptr.  The range bounds of up to
-        // 64 consecutive chunks sit one per lane in ptr_lo / ptr_hi and are read with v_readlane.
+        // 64 consecutive chunks sit one per lane in ptr_pk and are read with v_readlane.
         // (Loaded first: they are on the way while the tables below are set up.)
         const int ptr_max = a.row_len - 1;               // last entry of a row: end of the block's records
         const uint32_t *__restrict__ ptr_row = a.chan_ptr + size_t(active ? fblk : 0) * a.row_len;
         int win_base = c_begin;
-        uint32_t ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, ptr_max)];
-        uint32_t ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, ptr_max)];
+        // one register holds both bounds: first record (24 bits) and number of records (8 bits)
+        auto load_bounds = [&]() {
+            const uint32_t lo = ptr_row[min((win_base + lane) * CH + sub_lo, ptr_max)];
+            const uint32_t hi = ptr_row[min((win_base + lane) * CH + sub_hi, ptr_max)];
+            return lo << 8 | (hi - lo);
+        };
+        uint32_t ptr_pk = load_bounds();
         // The epilogue needs each slot's filter index and bias: two dependent loads, started here and
         // parked in LDS so that they cost the epilogue nothing (and no registers in between).
         float *out_tab = lds + S::OFF_OUT + wave * (2 * FB);
@@ -410,12 +415,12 @@ conv_tiled_kernel(const TiledArgs a)
         auto fetch_records = [&](int chunk, uint32_t &k0, uint32_t &k_cnt, uint32_t &rec_m, float4 &rec_w) {
             if (chunk - win_base > 63) {                 // every 64 chunks: next window of bounds
                 win_base = chunk;
-                ptr_lo = ptr_row[min((win_base + lane) * CH + sub_lo, ptr_max)];
-                ptr_hi = ptr_row[min((win_base + lane) * CH + sub_hi, ptr_max)];
+                ptr_pk = load_bounds();
                 __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0) here, so that the common path needs no wait
             }
-            k0 = __builtin_amdgcn_readlane(ptr_lo, chunk - win_base);
-            k_cnt = active ? __builtin_amdgcn_readlane(ptr_hi, chunk - win_base) - k0 : 0u;
+            const uint32_t pk = __builtin_amdgcn_readlane(ptr_pk, chunk - win_base);
+            k0 = pk >> 8;
+            k_cnt = active ? pk & 0xFFu : 0u;
 
             const uint32_t ridx = k0 + min(uint32_t(lane), k_cnt);
             rec_m = a.meta[ridx];
@@ -428,21 +433,20 @@ conv_tiled_kernel(const TiledArgs a)
             // (one loop around a single copy of the assembly: the refill of a further batch sits behind it)
             uint32_t base = 0;
             while (base < k_cnt) {
-                const uint32_t nb = min(uint32_t(BATCH), k_cnt - base);
+                const uint32_t nb = __builtin_amdgcn_readfirstlane(min(uint32_t(BATCH), k_cnt - base));
                 // lane j = record j of the batch; the lanes behind the last record end the list
                 const uint32_t rm = uint32_t(fresh_lane()) < nb ? rec_m : kMetaEndOfList;
-                uint32_t first = 0;                      // (kept apart from other zero operands)
-                asm volatile("" : "+s"(first));
+                const uint32_t koff = __builtin_amdgcn_readfirstlane((k0 + base) * 4u);
                 asm volatile(
 #include "pconv_tiled_compute.inc"
                     : "+{v[64:79]}"(acc[0]), "+{v[80:95]}"(acc[1]), "+{v[96:111]}"(acc[2]), "+{v[112:127]}"(acc[3])
                     : [recm] "v"(rm), [va] "v"(lds_base + buf_bytes + uint32_t(fresh_lane()) * 16u),
-                      [wa] "s"(wa), [first] "s"(first), [chmask] "n"(CH - 1)
+                      [wa] "s"(wa), [mp] "s"(a.meta), [koff] "s"(koff), [nb] "s"(nb), [chmask] "n"(CH - 1)
                     : "v22", "v23", "v24", "v25", "v26", "v27", "v28", "v29", "v30", "v31", "v32", "v33",
                       "v34", "v35", "v36", "v37", "v38", "v39", "v40", "v41", "v42", "v43", "v44", "v45",
                       "v46", "v47", "v48", "v49", "v50", "v51", "v52", "v53", "v54", "v55", "v56", "v57",
                       "v58", "v59", "v60", "v61", "v62", "v63",
-                      "s84", "s85", "s90", "s91", "s92", "s93", "s94", "s95", "scc");
+                      "s84", "s85", "s86", "s90", "s91", "s92", "s93", "s94", "s95", "scc");
                 // No "memory" clobber on purpose: it would make the compiler wait for the
                 // global->LDS loads of the next chunk, which may be in flight here and go to the
                 // other buffer.  What the loop reads was published before (barrier / counters), or
