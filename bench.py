@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes of the 13 conv launches of one step, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled
 # by a 256 MiB device copy (x2.000 / x1.000); see profiles/pconv_conv2d_vgg16_stack_n32_fp32.md.
 # Valid for the default workload (batch 32) only.
-MEASURED_TRAFFIC_BYTES_BATCH32 = 3.346e9
+MEASURED_TRAFFIC_BYTES_BATCH32 = 2.914e9
 
 
 def main():
