@@ -484,8 +484,8 @@ conv_tiled_kernel(const TiledArgs a)
             // waves may be one chunk apart, so a chunk costs a wave its own records, not the records of
             // the busiest wave, and the staging falls to the waves with the least to do.  The slowest
             // wave never waits for a faster one: whatever it needs has been, or can be, produced by
-            // itself.  Waits are bounded (kSpinLimit) so that a mistake here ends in wrong results, not
-            // in a hang.
+            // itself.  Waits are bounded (TiledArgs::spin_limit polls) so that a mistake here ends in an
+            // error code and poisoned outputs, not in a hang.
             unsigned *tickets = sync_words, *staged = sync_words + 2, *done = sync_words + 4;
             // A wait that runs out marks the workgroup (every wave poisons its outputs with NaN in
             // the epilogue) and leaves a code in the handle's error word, which the next call on
